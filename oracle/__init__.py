@@ -1,0 +1,170 @@
+"""CPU oracle for fast reciprocal nearest-neighbour matching -- TEST INFRASTRUCTURE ONLY.
+
+Only ``tests/``, ``__graft_entry__.smoke()`` and the ``cpu_baseline`` leg of ``bench.py``
+may import this package.  It shares no code with the HIP library and never imports it.
+
+What each function follows:
+
+* ``nearest``       -- the per-pixel reading of the paper's Algorithm 1 (section 3.4.3):
+                       brute force over all candidates, strict improvement, lowest index
+                       on ties, score = dot product in fp32 (C, ``fnn_oracle.c``).
+* ``mutual_dense``  -- the "traditional mutual nearest neighbour" definition the paper
+                       contrasts FastNN with (section 3.2, "Problem Context"): a pair
+                       (i, j) is kept when j is i's best candidate and i is j's.
+* ``reciprocal``    -- the FastNN iteration (section 3.2, "FastNN Algorithm", steps 1-4),
+                       step by step: U^0 = seeds, V^0 = NN_2(U^0); each iteration
+                       U^{t+1} = NN_1(V^t), matches M_t are the seeds with
+                       U^{t+1} = U^t, converged seeds leave, M is the union of the M_t.
+
+Readings where the paper is silent (all also listed in the design doc): dist_func is the
+negated dot product; ties go to the lowest index; a seed n with U^{t+1}[n] == U^t[n]
+contributes the pair (U^t[n], V^t[n]); the loop stops only when every seed has converged
+or after ``max_iter`` iterations; unconverged seeds are reported with iter = -1 and are
+not in M; M is returned as a sorted set.
+
+Pins: see tests/test_oracle_*.py (numpy/scipy library routines on exactly representable
+inputs, closed forms, a hand-worked score-matrix example, exhaustive enumeration on tiny
+inputs, invariants).
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import numpy as np
+
+from . import build as _build
+
+_lib = None
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        path = _build.LIB_PATH
+        if not os.path.exists(path):
+            path = _build.build()
+        lib = ctypes.CDLL(path)
+        lib.oracle_nearest.restype = None
+        lib.oracle_nearest.argtypes = [
+            ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32,
+            ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+        ]
+        lib.oracle_threads.restype = ctypes.c_int32
+        lib.oracle_threads.argtypes = []
+        _lib = lib
+    return _lib
+
+
+def threads() -> int:
+    """Number of host threads ``nearest`` runs on."""
+    return int(_load().oracle_threads())
+
+
+def round_fp16(x: np.ndarray) -> np.ndarray:
+    """fp32 -> IEEE binary16 (round to nearest even) -> fp32."""
+    return np.asarray(x, dtype=np.float32).astype(np.float16).astype(np.float32)
+
+
+def round_bf16(x: np.ndarray) -> np.ndarray:
+    """fp32 -> bfloat16 (round to nearest even; finite inputs) -> fp32."""
+    u = np.ascontiguousarray(x, dtype=np.float32).view(np.uint32).astype(np.uint64)
+    u = u + np.uint64(0x7FFF) + ((u >> np.uint64(16)) & np.uint64(1))
+    u = (u & np.uint64(0xFFFF0000)).astype(np.uint32)
+    return u.view(np.float32).reshape(np.shape(x))
+
+
+def nearest(a: np.ndarray, b: np.ndarray):
+    """For every row of ``a``: lowest index of the row of ``b`` with the largest dot product.
+
+    Returns (idx int32[K], best float32[K], second float32[K]); ``best - second`` is the
+    top-1/top-2 gap (0 on a tie).
+    """
+    a = np.ascontiguousarray(a, dtype=np.float32)
+    b = np.ascontiguousarray(b, dtype=np.float32)
+    assert a.ndim == 2 and b.ndim == 2 and a.shape[1] == b.shape[1]
+    k, d = a.shape
+    m = b.shape[0]
+    idx = np.empty(k, dtype=np.int32)
+    best = np.empty(k, dtype=np.float32)
+    second = np.empty(k, dtype=np.float32)
+    _load().oracle_nearest(a.ctypes.data, k, b.ctypes.data, m, d,
+                           idx.ctypes.data, best.ctypes.data, second.ctypes.data)
+    return idx, best, second
+
+
+def mutual_dense(d1: np.ndarray, d2: np.ndarray):
+    """All-pairs mutual nearest neighbours.
+
+    Returns a dict with nn12/s12/gap12 (best candidate in d2 for every row of d1),
+    nn21/s21/gap21 (the other direction) and ``pairs`` int32[P][2], the (i, nn12[i]) with
+    nn21[nn12[i]] == i, ascending in i.
+    """
+    nn12, s12, r12 = nearest(d1, d2)
+    nn21, s21, r21 = nearest(d2, d1)
+    i = np.arange(d1.shape[0], dtype=np.int32)
+    keep = (nn12 >= 0)
+    keep[keep] = nn21[nn12[keep]] == i[keep]
+    pairs = np.stack([i[keep], nn12[keep]], axis=1).astype(np.int32)
+    return {
+        "nn12": nn12, "s12": s12, "gap12": s12 - r12,
+        "nn21": nn21, "s21": s21, "gap21": s21 - r21,
+        "pairs": pairs,
+    }
+
+
+def reciprocal(d1: np.ndarray, d2: np.ndarray, seeds: np.ndarray, max_iter: int):
+    """The FastNN iteration from the given seed pixels of image 1.
+
+    Returns a dict:
+      seed_i, seed_j, seed_iter  int32[n_seeds]  per seed: the pair it converged to and the
+                                 iteration t at which U^{t+1} == U^t held; iter == -1 for a
+                                 seed still moving after ``max_iter`` iterations, with
+                                 (seed_i, seed_j) its last state (U^{T-1}, V^{T-1})
+      pairs     int32[P][2]      M = union of the M_t, as a set sorted by (i, j)
+      min_gap   float32[n_seeds] smallest top-1/top-2 gap over every search the seed took
+                                 part in (tells which seeds a rounding difference may move)
+      active    list[int]        number of queries in each search, in order
+    """
+    d1 = np.ascontiguousarray(d1, dtype=np.float32)
+    d2 = np.ascontiguousarray(d2, dtype=np.float32)
+    seeds = np.asarray(seeds, dtype=np.int32)
+    n = seeds.shape[0]
+    u = seeds.copy()                                   # U^t
+    v = np.full(n, -1, dtype=np.int32)                 # V^t
+    seed_iter = np.full(n, -1, dtype=np.int32)
+    min_gap = np.full(n, np.inf, dtype=np.float32)
+    searches = []
+
+    act = np.arange(n)
+    if n:
+        # step 1: V^0 = NN_2(U^0)
+        v[act], best, second = nearest(d1[u[act]], d2)
+        min_gap[act] = np.minimum(min_gap[act], best - second)
+        searches.append(int(act.size))
+    for t in range(max_iter):
+        if act.size == 0:
+            break
+        # step 2: U^{t+1} = NN_1(V^t)
+        u_next, best, second = nearest(d2[v[act]], d1)
+        min_gap[act] = np.minimum(min_gap[act], best - second)
+        searches.append(int(act.size))
+        conv = u_next == u[act]
+        seed_iter[act[conv]] = t                       # M_t: (U^t[n], V^t[n]) for these n
+        moved = ~conv
+        u_next = u_next[moved]
+        act = act[moved]                               # converged seeds leave
+        if act.size == 0 or t == max_iter - 1:
+            break
+        u[act] = u_next
+        v[act], best, second = nearest(d1[u[act]], d2)   # V^{t+1} = NN_2(U^{t+1})
+        min_gap[act] = np.minimum(min_gap[act], best - second)
+        searches.append(int(act.size))
+
+    done = seed_iter >= 0
+    if done.any():
+        pairs = np.unique(np.stack([u[done], v[done]], axis=1), axis=0).astype(np.int32)
+    else:
+        pairs = np.zeros((0, 2), dtype=np.int32)
+    return {"seed_i": u, "seed_j": v, "seed_iter": seed_iter, "pairs": pairs,
+            "min_gap": min_gap, "active": searches}

@@ -1,0 +1,64 @@
+/*
+ * CPU oracle for fast reciprocal nearest-neighbour matching -- TEST INFRASTRUCTURE ONLY.
+ *
+ * Plain, slow, obviously-correct reference for what the GPU library computes.  It shares
+ * no code with the HIP path; only tests, the smoke check and the benchmark's CPU-baseline
+ * leg may call it.
+ *
+ * oracle_nearest is the one-directional search of the paper's Algorithm 1 ("Original
+ * FastNN", section 3.4.3) taken per pixel: an outer loop over the queries, an inner loop
+ * over all candidates in ascending index order, a running best that is replaced only on a
+ * STRICT improvement -- so the lowest candidate index wins ties.  The distance function is
+ * the negated dot product (the paper leaves dist_func open; the workload fixes it), hence
+ * "dist < min_dist" becomes "score > best".
+ *
+ * Arithmetic: fp32, k ascending, accumulator starts at +0.0f, no FMA contraction and no
+ * reassociation (compile with -ffp-contract=off -fno-fast-math).
+ */
+#include <math.h>
+#include <stdint.h>
+
+/*
+ * a      [k_rows][d]  queries, row-major fp32
+ * b      [m_rows][d]  candidates, row-major fp32
+ * idx    [k_rows]     out: lowest index of the best candidate (-1 when m_rows == 0)
+ * best   [k_rows]     out: its score (-inf when m_rows == 0)
+ * second [k_rows]     out: the best score among the other candidates; a tied duplicate
+ *                          counts, so best-second == 0 on a tie (-inf when m_rows < 2)
+ */
+void oracle_nearest(const float* a, int64_t k_rows, const float* b, int64_t m_rows, int32_t d,
+                    int32_t* idx, float* best, float* second)
+{
+#pragma omp parallel for schedule(dynamic, 16)
+    for (int64_t q = 0; q < k_rows; ++q) {
+        const float* aq = a + q * (int64_t)d;
+        float top = -INFINITY, runner_up = -INFINITY;
+        int32_t top_j = -1;
+        for (int64_t j = 0; j < m_rows; ++j) {
+            const float* bj = b + j * (int64_t)d;
+            float s = 0.0f;
+            for (int32_t k = 0; k < d; ++k) {
+                float p = aq[k] * bj[k];
+                s = s + p;
+            }
+            if (s > top) {
+                runner_up = top;
+                top = s;
+                top_j = (int32_t)j;
+            } else if (s > runner_up) {
+                runner_up = s;
+            }
+        }
+        idx[q] = top_j;
+        best[q] = top;
+        second[q] = runner_up;
+    }
+}
+
+/* Number of threads the parallel loop above uses (for the benchmark's report). */
+#ifdef _OPENMP
+#include <omp.h>
+int32_t oracle_threads(void) { return (int32_t)omp_get_max_threads(); }
+#else
+int32_t oracle_threads(void) { return 1; }
+#endif
