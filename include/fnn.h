@@ -1,0 +1,147 @@
+/*
+ * fnn.h -- C ABI of libfnn: fast reciprocal nearest-neighbour matching between two dense
+ * per-pixel descriptor maps on one AMD Instinct MI355X (gfx950).
+ *
+ * The three operations are the matching stage of the Speedy MASt3R paper (arXiv 2503.10017):
+ *
+ *   fnn_nearest       one-directional search: for every query pixel the candidate pixel with
+ *                     the best score.  This is the search of Algorithm 1 / Algorithm 2
+ *                     ("FastNN-Lite", section 3.4.3) with the mixed-precision rule of
+ *                     Algorithm 3 ("HybridCast", section 3.4.4): descriptors may be rounded
+ *                     to a 16-bit format, products are accumulated and the best candidate
+ *                     is selected in fp32.
+ *   fnn_reciprocal    the FastNN iteration (section 3.2, "FastNN Algorithm", steps 1-4):
+ *                     seeds in image 1, ping-pong searches, seeds leave when they return to
+ *                     where they were, the result is the set of reciprocal matches.
+ *   fnn_mutual_dense  the all-pairs mutual nearest neighbours that FastNN approximates
+ *                     (section 3.2, "Problem Context").
+ *
+ * Conventions shared by every entry point
+ * ---------------------------------------
+ *  - score(a, b) = sum_k a[k] * b[k]  (dist_func = negated dot product); the best candidate
+ *    has the LARGEST score and, among equal scores, the LOWEST index (the strict "<" update
+ *    of Algorithm 1).
+ *  - A map is a row-major [n][d] array in DEVICE memory, pixel id = y * W + x, rows
+ *    `row_stride` elements apart (row_stride >= d).  1 <= d <= FNN_MAX_D.
+ *    n <= 2^31 - 64.  Inputs must be finite; NaN/Inf give unspecified results.
+ *  - `batch` independent image pairs share shapes; maps are passed as HOST arrays of
+ *    `batch` fnn_map structs (1 <= batch <= FNN_MAX_BATCH); every other array is ONE
+ *    contiguous DEVICE buffer with the batch index outermost.
+ *  - The caller owns every buffer.  The library allocates nothing, keeps no state between
+ *    calls and touches only the outputs and `workspace` (device, >= fnn_workspace_bytes(),
+ *    256-byte aligned).  All work is enqueued on `stream` (a hipStream_t, NULL = default
+ *    stream) and the call returns without waiting; outputs are valid once the stream has
+ *    reached that point.  Two calls that share a workspace must be ordered by the stream.
+ *  - Errors are return codes only.  Argument errors are detected on the host before
+ *    anything is enqueued (outputs untouched).  Index arrays live in device memory and are
+ *    NOT range-checked: a seed or query index outside [0, n) is undefined behaviour.
+ *  - `compute` selects the format the descriptors are rounded to (round-to-nearest-even)
+ *    before multiplication: FNN_F16 / FNN_BF16 use the 16-bit matrix instructions,
+ *    FNN_F32 multiplies unrounded fp32 values.  Accumulation and selection are fp32 in
+ *    all three.  The summation order over k is unspecified.
+ */
+#ifndef FNN_H
+#define FNN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define FNN_MAX_D 32
+#define FNN_MAX_BATCH 64
+
+typedef enum {
+    FNN_OK = 0,
+    FNN_E_NULL = 1,        /* a required pointer is NULL */
+    FNN_E_SHAPE = 2,       /* batch, n, d, row_stride, nq, n_seeds out of range or inconsistent */
+    FNN_E_DTYPE = 3,       /* unknown storage or compute format */
+    FNN_E_RANGE = 4,       /* max_iter < 0 or another option out of range */
+    FNN_E_WORKSPACE = 5,   /* workspace NULL, misaligned or smaller than fnn_workspace_bytes() */
+    FNN_E_HIP = 6,         /* a HIP call or kernel launch failed */
+    FNN_E_UNSUPPORTED = 7  /* valid request this build cannot serve */
+} fnn_status;
+
+typedef enum { FNN_F32 = 0, FNN_F16 = 1, FNN_BF16 = 2 } fnn_dtype;
+
+/* One descriptor map.  `data` is a device pointer to n rows of d elements of `dtype`. */
+typedef struct {
+    const void* data;
+    int64_t n;
+    int32_t d;
+    int32_t dtype;        /* fnn_dtype of the stored elements */
+    int64_t row_stride;   /* in elements */
+} fnn_map;
+
+typedef struct {
+    int32_t compute;      /* fnn_dtype the products are formed in (see above) */
+    int32_t max_iter;     /* fnn_reciprocal only: T, the iteration cap (>= 0) */
+    int32_t reserved[6];  /* must be zero */
+} fnn_opts;
+
+/* Human-readable name of a status code (static storage). */
+const char* fnn_status_string(int32_t status);
+
+/*
+ * Bytes of device workspace sufficient for any of the three operations on `batch` pairs of
+ * maps with n and m pixels, d channels, at most `n_queries` queries or seeds per pair.
+ * Returns 0 when the shape is invalid.
+ */
+size_t fnn_workspace_bytes(int32_t batch, int64_t n, int64_t m, int32_t d, int64_t n_queries, int32_t compute);
+
+/*
+ * One-directional search (Algorithms 1-3).  For b < batch and q < nq:
+ *   row  = q_idx ? q_idx[b*nq + q] : q                 (a pixel of src[b]; needs nq <= src.n)
+ *   out_idx[b*nq + q]   = lowest j maximising score(src[b][row], tgt[b][j])
+ *   out_score[b*nq + q] = that score (fp32); out_score may be NULL.
+ * When nq_active (device int32[batch]) is not NULL only the first
+ * min(nq_active[b], nq) queries of pair b are searched and the rest of that pair's outputs
+ * are left untouched.  The N x M score matrix is never written to memory.
+ */
+int32_t fnn_nearest(int32_t batch, const fnn_map* src, const int32_t* q_idx, int64_t nq,
+                    const int32_t* nq_active, const fnn_map* tgt, const fnn_opts* opts,
+                    int32_t* out_idx, float* out_score,
+                    void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * The FastNN iteration (section 3.2).  seeds: device int32[batch][n_seeds], pixel ids of
+ * d1 (duplicates allowed).  With U^0 = seeds, V^0 = NN_2(U^0), then for t = 0..max_iter-1:
+ * U^{t+1} = NN_1(V^t); a seed with U^{t+1} == U^t has converged: it yields the match
+ * (U^t, V^t), records iteration t and leaves; the others continue with
+ * V^{t+1} = NN_2(U^{t+1}).  The loop stops when no seed is left or after max_iter
+ * iterations (at most 2*max_iter searches).
+ * Outputs (device):
+ *   seed_i, seed_j, seed_iter  int32[batch][n_seeds]: the match of each seed and the
+ *        iteration at which it converged; seed_iter == -1 marks a seed that was still moving
+ *        (the convergence mask) and (seed_i, seed_j) is then its last state (U^{T-1}, V^{T-1}).
+ *   pairs    int32[batch][n_seeds][2]: the matches of the converged seeds as a set, sorted
+ *        by (i, j); entries past n_pairs[b] are -1.
+ *   n_pairs  int32[batch].
+ */
+int32_t fnn_reciprocal(int32_t batch, const fnn_map* d1, const fnn_map* d2,
+                       const int32_t* seeds, int64_t n_seeds, const fnn_opts* opts,
+                       int32_t* seed_i, int32_t* seed_j, int32_t* seed_iter,
+                       int32_t* pairs, int32_t* n_pairs,
+                       void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * All-pairs mutual nearest neighbours (section 3.2, "Problem Context").  With
+ * S[i][j] = score(d1[i], d2[j]):
+ *   nn12[b][i] = lowest j maximising S[i][j],  s12 = that score      (int32/float [batch][n])
+ *   nn21[b][j] = lowest i maximising S[i][j],  s21 = that score      (int32/float [batch][m])
+ *   pairs[b]   = the (i, nn12[i]) with nn21[nn12[i]] == i, ascending in i
+ *                (int32[batch][min(n,m)][2], entries past n_pairs[b] are -1)
+ * Every S[i][j] is computed once and feeds both directions, so nn12 and nn21 are consistent
+ * with each other.  s12, s21 may be NULL.
+ */
+int32_t fnn_mutual_dense(int32_t batch, const fnn_map* d1, const fnn_map* d2, const fnn_opts* opts,
+                         int32_t* nn12, float* s12, int32_t* nn21, float* s21,
+                         int32_t* pairs, int32_t* n_pairs,
+                         void* workspace, size_t workspace_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FNN_H */

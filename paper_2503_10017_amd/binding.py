@@ -1,0 +1,219 @@
+"""ctypes binding of libfnn.so: argument marshalling only.
+
+Every function here has the name and meaning of the C entry point it wraps (see
+include/fnn.h).  torch supplies device memory and the current stream; all arithmetic of
+the matching path runs inside the library's kernels.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Sequence, Union
+
+import torch
+
+FNN_F32, FNN_F16, FNN_BF16 = 0, 1, 2
+FNN_MAX_D = 32
+FNN_MAX_BATCH = 64
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "lib", "libfnn.so")
+_lib = None
+
+
+class FnnError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: status {status} ({fnn_status_string(status)})")
+
+
+class _Map(ctypes.Structure):
+    _fields_ = [("data", ctypes.c_void_p), ("n", ctypes.c_int64), ("d", ctypes.c_int32),
+                ("dtype", ctypes.c_int32), ("row_stride", ctypes.c_int64)]
+
+
+class _Opts(ctypes.Structure):
+    _fields_ = [("compute", ctypes.c_int32), ("max_iter", ctypes.c_int32), ("reserved", ctypes.c_int32 * 6)]
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def load_library():
+    """Load lib/libfnn.so (built by ``paper_2503_10017_amd.build``); raises if it is missing."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise RuntimeError(f"{_LIB_PATH} is missing: build it with `python -m paper_2503_10017_amd.build` "
+                           "(there is no fallback implementation)")
+    lib = ctypes.CDLL(_LIB_PATH)
+    vp, i32, i64, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_size_t
+    lib.fnn_status_string.restype = ctypes.c_char_p
+    lib.fnn_status_string.argtypes = [i32]
+    lib.fnn_workspace_bytes.restype = sz
+    lib.fnn_workspace_bytes.argtypes = [i32, i64, i64, i32, i64, i32]
+    lib.fnn_nearest.restype = i32
+    lib.fnn_nearest.argtypes = [i32, vp, vp, i64, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.fnn_reciprocal.restype = i32
+    lib.fnn_reciprocal.argtypes = [i32, vp, vp, vp, i64, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.fnn_mutual_dense.restype = i32
+    lib.fnn_mutual_dense.argtypes = [i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    _lib = lib
+    return lib
+
+
+def fnn_status_string(status: int) -> str:
+    return load_library().fnn_status_string(int(status)).decode()
+
+
+_DTYPES = {torch.float32: FNN_F32, torch.float16: FNN_F16, torch.bfloat16: FNN_BF16}
+_COMPUTE = {"f32": FNN_F32, "fp32": FNN_F32, "f16": FNN_F16, "fp16": FNN_F16, "bf16": FNN_BF16,
+            FNN_F32: FNN_F32, FNN_F16: FNN_F16, FNN_BF16: FNN_BF16}
+
+MapsLike = Union[torch.Tensor, Sequence[torch.Tensor]]
+
+
+def _as_pairs(maps: MapsLike):
+    """[n][d] tensor, [batch][n][d] tensor or a sequence of [n][d] tensors -> list of 2-D views."""
+    if isinstance(maps, torch.Tensor):
+        if maps.dim() == 2:
+            return [maps]
+        if maps.dim() == 3:
+            return [maps[b] for b in range(maps.shape[0])]
+        raise ValueError("a map is [n][d] or [batch][n][d]")
+    return list(maps)
+
+
+def _map_array(views):
+    arr = (_Map * len(views))()
+    for b, t in enumerate(views):
+        if t.dim() != 2 or not t.is_cuda:
+            raise ValueError("maps must be 2-D device tensors")
+        if t.dtype not in _DTYPES:
+            raise ValueError(f"unsupported map dtype {t.dtype}")
+        if t.shape[1] > 1 and t.stride(1) != 1:
+            raise ValueError("channels of a map must be contiguous")
+        arr[b].data = t.data_ptr()
+        arr[b].n = t.shape[0]
+        arr[b].d = t.shape[1]
+        arr[b].dtype = _DTYPES[t.dtype]
+        arr[b].row_stride = t.stride(0) if t.shape[0] > 1 else max(t.shape[1], t.stride(0))
+    return arr
+
+
+def _opts(compute, max_iter=0):
+    o = _Opts()
+    o.compute = _COMPUTE[compute]
+    o.max_iter = int(max_iter)
+    return o
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream_ptr(stream, device):
+    if stream is None:
+        stream = torch.cuda.current_stream(device)
+    return ctypes.c_void_p(stream.cuda_stream)
+
+
+def fnn_workspace_bytes(batch: int, n: int, m: int, d: int, n_queries: int, compute) -> int:
+    return int(load_library().fnn_workspace_bytes(batch, n, m, d, n_queries, _COMPUTE[compute]))
+
+
+def _workspace(workspace, need, device):
+    if workspace is None:
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=device)
+    return workspace
+
+
+def fnn_nearest(src: MapsLike, tgt: MapsLike, q_idx: Optional[torch.Tensor] = None,
+                nq: Optional[int] = None, nq_active: Optional[torch.Tensor] = None, compute="f16",
+                out_idx: Optional[torch.Tensor] = None, out_score: Optional[torch.Tensor] = None,
+                want_score: bool = True, workspace: Optional[torch.Tensor] = None, stream=None):
+    """One-directional search; returns (out_idx int32[batch][nq], out_score float32[batch][nq] or None)."""
+    lib = load_library()
+    sv, tv = _as_pairs(src), _as_pairs(tgt)
+    batch = len(sv)
+    device = sv[0].device
+    if nq is None:
+        nq = q_idx.shape[-1] if q_idx is not None else sv[0].shape[0]
+    if out_idx is None:
+        out_idx = torch.empty((batch, nq), dtype=torch.int32, device=device)
+    if out_score is None and want_score:
+        out_score = torch.empty((batch, nq), dtype=torch.float32, device=device)
+    need = fnn_workspace_bytes(batch, sv[0].shape[0], tv[0].shape[0], sv[0].shape[1], nq, compute)
+    workspace = _workspace(workspace, need, device)
+    o = _opts(compute)
+    sa, ta = _map_array(sv), _map_array(tv)
+    st = lib.fnn_nearest(batch, ctypes.cast(sa, ctypes.c_void_p), _ptr(q_idx), nq, _ptr(nq_active),
+                         ctypes.cast(ta, ctypes.c_void_p), ctypes.byref(o), _ptr(out_idx), _ptr(out_score),
+                         _ptr(workspace), workspace.numel(), _stream_ptr(stream, device))
+    if st != 0:
+        raise FnnError(st, "fnn_nearest")
+    return out_idx, out_score
+
+
+def fnn_reciprocal(d1: MapsLike, d2: MapsLike, seeds: torch.Tensor, max_iter: int = 10, compute="f16",
+                   out: Optional[dict] = None, workspace: Optional[torch.Tensor] = None, stream=None):
+    """The FastNN iteration; returns a dict of device tensors
+    seed_i, seed_j, seed_iter [batch][n_seeds], pairs [batch][n_seeds][2], n_pairs [batch]."""
+    lib = load_library()
+    v1, v2 = _as_pairs(d1), _as_pairs(d2)
+    batch = len(v1)
+    device = v1[0].device
+    n_seeds = seeds.shape[-1]
+    if out is None:
+        out = {
+            "seed_i": torch.empty((batch, n_seeds), dtype=torch.int32, device=device),
+            "seed_j": torch.empty((batch, n_seeds), dtype=torch.int32, device=device),
+            "seed_iter": torch.empty((batch, n_seeds), dtype=torch.int32, device=device),
+            "pairs": torch.empty((batch, n_seeds, 2), dtype=torch.int32, device=device),
+            "n_pairs": torch.empty((batch,), dtype=torch.int32, device=device),
+        }
+    need = fnn_workspace_bytes(batch, v1[0].shape[0], v2[0].shape[0], v1[0].shape[1], n_seeds, compute)
+    workspace = _workspace(workspace, need, device)
+    o = _opts(compute, max_iter)
+    a1, a2 = _map_array(v1), _map_array(v2)
+    st = lib.fnn_reciprocal(batch, ctypes.cast(a1, ctypes.c_void_p), ctypes.cast(a2, ctypes.c_void_p),
+                            _ptr(seeds), n_seeds, ctypes.byref(o),
+                            _ptr(out["seed_i"]), _ptr(out["seed_j"]), _ptr(out["seed_iter"]),
+                            _ptr(out["pairs"]), _ptr(out["n_pairs"]),
+                            _ptr(workspace), workspace.numel(), _stream_ptr(stream, device))
+    if st != 0:
+        raise FnnError(st, "fnn_reciprocal")
+    return out
+
+
+def fnn_mutual_dense(d1: MapsLike, d2: MapsLike, compute="f16", out: Optional[dict] = None,
+                     workspace: Optional[torch.Tensor] = None, stream=None):
+    """All-pairs mutual nearest neighbours; returns a dict of device tensors
+    nn12, s12 [batch][n], nn21, s21 [batch][m], pairs [batch][min(n,m)][2], n_pairs [batch]."""
+    lib = load_library()
+    v1, v2 = _as_pairs(d1), _as_pairs(d2)
+    batch = len(v1)
+    device = v1[0].device
+    n, m = v1[0].shape[0], v2[0].shape[0]
+    if out is None:
+        out = {
+            "nn12": torch.empty((batch, n), dtype=torch.int32, device=device),
+            "s12": torch.empty((batch, n), dtype=torch.float32, device=device),
+            "nn21": torch.empty((batch, m), dtype=torch.int32, device=device),
+            "s21": torch.empty((batch, m), dtype=torch.float32, device=device),
+            "pairs": torch.empty((batch, min(n, m), 2), dtype=torch.int32, device=device),
+            "n_pairs": torch.empty((batch,), dtype=torch.int32, device=device),
+        }
+    need = fnn_workspace_bytes(batch, n, m, v1[0].shape[1], 0, compute)
+    workspace = _workspace(workspace, need, device)
+    o = _opts(compute)
+    a1, a2 = _map_array(v1), _map_array(v2)
+    st = lib.fnn_mutual_dense(batch, ctypes.cast(a1, ctypes.c_void_p), ctypes.cast(a2, ctypes.c_void_p),
+                              ctypes.byref(o), _ptr(out["nn12"]), _ptr(out.get("s12")), _ptr(out["nn21"]),
+                              _ptr(out.get("s21")), _ptr(out["pairs"]), _ptr(out["n_pairs"]),
+                              _ptr(workspace), workspace.numel(), _stream_ptr(stream, device))
+    if st != 0:
+        raise FnnError(st, "fnn_mutual_dense")
+    return out

@@ -1,0 +1,407 @@
+// C entry points of libfnn (see include/fnn.h): argument checks, workspace carving and the
+// fixed kernel sequences.  Nothing here synchronises with the device or allocates memory.
+#include <string.h>
+
+#include "fnn_kernels.hpp"
+
+using namespace fnn;
+
+namespace {
+
+constexpr int64_t MAX_PIXELS = 2147483647LL - 64;
+constexpr size_t WS_ALIGN = 256;
+
+struct Carver {
+    char* base;
+    size_t used;
+    void* take(size_t bytes) {
+        void* p = base ? base + used : nullptr;
+        used += (bytes + WS_ALIGN - 1) / WS_ALIGN * WS_ALIGN;
+        return p;
+    }
+};
+
+int64_t pow2_at_least(int64_t x) {
+    int64_t p = 1;
+    while (p < x) p <<= 1;
+    return p;
+}
+
+bool valid_dtype(int32_t t) { return t == FNN_F32 || t == FNN_F16 || t == FNN_BF16; }
+
+struct MapsLayout {
+    void* p1;
+    void* p2;
+    int64_t n_pad, m_pad;
+    int64_t bstride1, bstride2;  // bytes per pair
+    int dp;
+};
+
+MapsLayout carve_maps(Carver& cv, int batch, int64_t n, int64_t m, int d, int compute) {
+    MapsLayout L;
+    L.dp = padded_d(d, compute);
+    L.n_pad = round_up(n, 32);
+    L.m_pad = round_up(m, 32);
+    const int es = elem_size(compute);
+    L.bstride1 = L.n_pad * L.dp * es;
+    L.bstride2 = L.m_pad * L.dp * es;
+    L.p1 = cv.take((size_t)batch * L.bstride1);
+    L.p2 = cv.take((size_t)batch * L.bstride2);
+    return L;
+}
+
+struct NearestLayout {
+    MapsLayout maps;
+    u64* keys;
+};
+NearestLayout carve_nearest(Carver& cv, int batch, int64_t n, int64_t m, int d, int64_t nq, int compute) {
+    NearestLayout L;
+    L.maps = carve_maps(cv, batch, n, m, d, compute);
+    L.keys = (u64*)cv.take((size_t)batch * nq * sizeof(u64));
+    return L;
+}
+
+struct RecipLayout {
+    MapsLayout maps;
+    RecipState st;
+};
+RecipLayout carve_recip(Carver& cv, int batch, int64_t n, int64_t m, int d, int64_t n_seeds, int compute) {
+    RecipLayout L;
+    L.maps = carve_maps(cv, batch, n, m, d, compute);
+    const size_t per = (size_t)batch * n_seeds;
+    L.st.keys_f = (u64*)cv.take(per * sizeof(u64));
+    L.st.keys_b = (u64*)cv.take(per * sizeof(u64));
+    L.st.cur_u[0] = (int32_t*)cv.take(per * sizeof(int32_t));
+    L.st.cur_u[1] = (int32_t*)cv.take(per * sizeof(int32_t));
+    L.st.seed_id[0] = (int32_t*)cv.take(per * sizeof(int32_t));
+    L.st.seed_id[1] = (int32_t*)cv.take(per * sizeof(int32_t));
+    L.st.n_active = (int32_t*)cv.take((size_t)batch * sizeof(int32_t));
+    L.st.sort_len = pow2_at_least(n_seeds > 1 ? n_seeds : 1);
+    L.st.sort_buf = (u64*)cv.take((size_t)batch * L.st.sort_len * sizeof(u64));
+    return L;
+}
+
+struct DenseLayout {
+    MapsLayout maps;
+    u64* row_keys;
+    u64* col_keys;
+    int32_t* block_counts;
+    int64_t blocks_per_pair;
+};
+DenseLayout carve_dense(Carver& cv, int batch, int64_t n, int64_t m, int d, int compute) {
+    DenseLayout L;
+    L.maps = carve_maps(cv, batch, n, m, d, compute);
+    // the two key tables are adjacent so that one fill clears both
+    L.row_keys = (u64*)cv.take((size_t)batch * (n + m) * sizeof(u64));
+    L.col_keys = L.row_keys ? L.row_keys + (size_t)batch * n : nullptr;
+    const int64_t most = n > m ? n : m;
+    L.blocks_per_pair = (most + 1023) / 1024;
+    L.block_counts = (int32_t*)cv.take((size_t)batch * (L.blocks_per_pair + 1) * sizeof(int32_t));
+    return L;
+}
+
+bool shape_ok(int32_t batch, int64_t n, int64_t m, int32_t d, int64_t nq) {
+    return batch >= 1 && batch <= FNN_MAX_BATCH && n >= 0 && m >= 0 && n <= MAX_PIXELS && m <= MAX_PIXELS &&
+           d >= 1 && d <= FNN_MAX_D && nq >= 0 && nq <= MAX_PIXELS;
+}
+
+// Checks a host array of `batch` maps that must share shape and format.
+int32_t check_maps(int32_t batch, const fnn_map* maps) {
+    if (!maps) return FNN_E_NULL;
+    for (int b = 0; b < batch; ++b) {
+        const fnn_map& mp = maps[b];
+        if (!valid_dtype(mp.dtype)) return FNN_E_DTYPE;
+        if (mp.n < 0 || mp.n > MAX_PIXELS || mp.d < 1 || mp.d > FNN_MAX_D || mp.row_stride < mp.d) return FNN_E_SHAPE;
+        if (mp.n != maps[0].n || mp.d != maps[0].d || mp.dtype != maps[0].dtype || mp.row_stride != maps[0].row_stride)
+            return FNN_E_SHAPE;
+        if (mp.n > 0 && !mp.data) return FNN_E_NULL;
+    }
+    return FNN_OK;
+}
+
+int32_t check_opts(const fnn_opts* o) {
+    if (!o) return FNN_E_NULL;
+    if (!valid_dtype(o->compute)) return FNN_E_DTYPE;
+    if (o->max_iter < 0) return FNN_E_RANGE;
+    for (int i = 0; i < 6; ++i)
+        if (o->reserved[i] != 0) return FNN_E_RANGE;
+    return FNN_OK;
+}
+
+int32_t check_workspace(const void* ws, size_t have, size_t need) {
+    if (need == 0) return FNN_OK;
+    if (!ws || ((uintptr_t)ws % WS_ALIGN) != 0 || have < need) return FNN_E_WORKSPACE;
+    return FNN_OK;
+}
+
+void fill_prep_side(PrepSide& sd, int32_t batch, const fnn_map* maps, int64_t n_pad, void* dst) {
+    memset(&sd, 0, sizeof(sd));
+    for (int b = 0; b < batch; ++b) sd.src[b] = maps[b].data;
+    sd.n = maps[0].n;
+    sd.n_pad = n_pad;
+    sd.row_stride = maps[0].row_stride;
+    sd.dtype = maps[0].dtype;
+    sd.dst = dst;
+}
+
+hipError_t prep_both(int32_t batch, const fnn_map* a, const fnn_map* b, const MapsLayout& L, int d, int compute,
+                     hipStream_t s) {
+    PrepArgs pa;
+    memset(&pa, 0, sizeof(pa));
+    fill_prep_side(pa.side[0], batch, a, L.n_pad, L.p1);
+    fill_prep_side(pa.side[1], batch, b, L.m_pad, L.p2);
+    pa.n_sides = 2;
+    pa.batch = batch;
+    pa.d = d;
+    pa.dp = L.dp;
+    pa.compute = compute;
+    return launch_prep(pa, s);
+}
+
+#define FNN_TRY(expr)                        \
+    do {                                     \
+        if ((expr) != hipSuccess) return FNN_E_HIP; \
+    } while (0)
+
+}  // namespace
+
+#pragma GCC visibility push(default)
+extern "C" {
+
+const char* fnn_status_string(int32_t status) {
+    switch (status) {
+        case FNN_OK: return "ok";
+        case FNN_E_NULL: return "a required pointer is NULL";
+        case FNN_E_SHAPE: return "shape out of range or inconsistent";
+        case FNN_E_DTYPE: return "unknown storage or compute format";
+        case FNN_E_RANGE: return "option out of range";
+        case FNN_E_WORKSPACE: return "workspace missing, misaligned or too small";
+        case FNN_E_HIP: return "a HIP call or kernel launch failed";
+        case FNN_E_UNSUPPORTED: return "request not supported by this build";
+        default: return "unknown status";
+    }
+}
+
+size_t fnn_workspace_bytes(int32_t batch, int64_t n, int64_t m, int32_t d, int64_t n_queries, int32_t compute) {
+    if (!shape_ok(batch, n, m, d, n_queries) || !valid_dtype(compute)) return 0;
+    size_t most = 0;
+    {
+        Carver cv{nullptr, 0};
+        carve_nearest(cv, batch, n, m, d, n_queries, compute);
+        most = cv.used;
+    }
+    {
+        Carver cv{nullptr, 0};
+        carve_recip(cv, batch, n, m, d, n_queries, compute);
+        if (cv.used > most) most = cv.used;
+    }
+    {
+        Carver cv{nullptr, 0};
+        carve_dense(cv, batch, n, m, d, compute);
+        if (cv.used > most) most = cv.used;
+    }
+    return most + WS_ALIGN;
+}
+
+int32_t fnn_nearest(int32_t batch, const fnn_map* src, const int32_t* q_idx, int64_t nq, const int32_t* nq_active,
+                    const fnn_map* tgt, const fnn_opts* opts, int32_t* out_idx, float* out_score, void* workspace,
+                    size_t workspace_bytes, void* stream) {
+    if (batch < 1 || batch > FNN_MAX_BATCH) return FNN_E_SHAPE;
+    int32_t st = check_maps(batch, src);
+    if (st != FNN_OK) return st;
+    st = check_maps(batch, tgt);
+    if (st != FNN_OK) return st;
+    st = check_opts(opts);
+    if (st != FNN_OK) return st;
+    const int64_t n = src[0].n, m = tgt[0].n;
+    const int32_t d = src[0].d;
+    if (tgt[0].d != d || nq < 0 || nq > MAX_PIXELS) return FNN_E_SHAPE;
+    if (!q_idx && nq > n) return FNN_E_SHAPE;
+    if (nq > 0 && n == 0) return FNN_E_SHAPE;
+    if (nq > 0 && !out_idx) return FNN_E_NULL;
+    if (nq == 0) return FNN_OK;
+
+    Carver cv{(char*)workspace, 0};
+    NearestLayout L = carve_nearest(cv, batch, n, m, d, nq, opts->compute);
+    st = check_workspace(workspace, workspace_bytes, cv.used);
+    if (st != FNN_OK) return st;
+    hipStream_t s = (hipStream_t)stream;
+
+    FNN_TRY(prep_both(batch, src, tgt, L.maps, d, opts->compute, s));
+    FNN_TRY(launch_fill_u64(L.keys, (int64_t)batch * nq, 0, s));
+    SearchArgs sa;
+    memset(&sa, 0, sizeof(sa));
+    sa.src = (const char*)L.maps.p1;
+    sa.src_bstride = L.maps.bstride1;
+    sa.src_rows = (int32_t)L.maps.n_pad;
+    sa.q_idx = q_idx;
+    sa.nq_active = nq_active;
+    sa.nq = (int32_t)nq;
+    sa.tgt = (const char*)L.maps.p2;
+    sa.tgt_bstride = L.maps.bstride2;
+    sa.m = (int32_t)m;
+    sa.m_tiles = (int32_t)(L.maps.m_pad / 32);
+    sa.out_keys = L.keys;
+    FNN_TRY(launch_search(sa, batch, opts->compute, L.maps.dp, s));
+    DecodeArgs da;
+    da.keys = L.keys;
+    da.nq_active = nq_active;
+    da.nq = (int32_t)nq;
+    da.out_idx = out_idx;
+    da.out_score = out_score;
+    FNN_TRY(launch_decode(da, batch, s));
+    return FNN_OK;
+}
+
+int32_t fnn_reciprocal(int32_t batch, const fnn_map* d1, const fnn_map* d2, const int32_t* seeds, int64_t n_seeds,
+                       const fnn_opts* opts, int32_t* seed_i, int32_t* seed_j, int32_t* seed_iter, int32_t* pairs,
+                       int32_t* n_pairs, void* workspace, size_t workspace_bytes, void* stream) {
+    if (batch < 1 || batch > FNN_MAX_BATCH) return FNN_E_SHAPE;
+    int32_t st = check_maps(batch, d1);
+    if (st != FNN_OK) return st;
+    st = check_maps(batch, d2);
+    if (st != FNN_OK) return st;
+    st = check_opts(opts);
+    if (st != FNN_OK) return st;
+    const int64_t n = d1[0].n, m = d2[0].n;
+    const int32_t d = d1[0].d;
+    if (d2[0].d != d || n_seeds < 0 || n_seeds > MAX_PIXELS) return FNN_E_SHAPE;
+    if (n_seeds > 0 && (n == 0 || m == 0)) return FNN_E_SHAPE;
+    if (!n_pairs) return FNN_E_NULL;
+    if (n_seeds > 0 && (!seeds || !seed_i || !seed_j || !seed_iter || !pairs)) return FNN_E_NULL;
+
+    Carver cv{(char*)workspace, 0};
+    RecipLayout L = carve_recip(cv, batch, n, m, d, n_seeds, opts->compute);
+    st = check_workspace(workspace, workspace_bytes, cv.used);
+    if (st != FNN_OK) return st;
+    hipStream_t s = (hipStream_t)stream;
+    const int compute = opts->compute;
+    const int32_t ns = (int32_t)n_seeds;
+
+    if (ns == 0) {
+        // nothing to match: only the counts are defined
+        FNN_TRY(launch_recip_dedup(L.st, 0, batch, seed_i, seed_j, seed_iter, pairs, n_pairs, s));
+        return FNN_OK;
+    }
+
+    FNN_TRY(prep_both(batch, d1, d2, L.maps, d, compute, s));
+    FNN_TRY(launch_recip_init(L.st, seeds, ns, batch, s));
+
+    SearchArgs fwd;  // queries in image 1 -> candidates in image 2
+    memset(&fwd, 0, sizeof(fwd));
+    fwd.src = (const char*)L.maps.p1;
+    fwd.src_bstride = L.maps.bstride1;
+    fwd.src_rows = (int32_t)L.maps.n_pad;
+    fwd.nq_active = L.st.n_active;
+    fwd.nq = ns;
+    fwd.tgt = (const char*)L.maps.p2;
+    fwd.tgt_bstride = L.maps.bstride2;
+    fwd.m = (int32_t)m;
+    fwd.m_tiles = (int32_t)(L.maps.m_pad / 32);
+    fwd.out_keys = L.st.keys_f;
+
+    SearchArgs bwd;  // queries in image 2 (named by the index field of keys_f) -> image 1
+    memset(&bwd, 0, sizeof(bwd));
+    bwd.src = (const char*)L.maps.p2;
+    bwd.src_bstride = L.maps.bstride2;
+    bwd.src_rows = (int32_t)L.maps.m_pad;
+    bwd.q_keys = L.st.keys_f;
+    bwd.nq_active = L.st.n_active;
+    bwd.nq = ns;
+    bwd.tgt = (const char*)L.maps.p1;
+    bwd.tgt_bstride = L.maps.bstride1;
+    bwd.m = (int32_t)n;
+    bwd.m_tiles = (int32_t)(L.maps.n_pad / 32);
+    bwd.out_keys = L.st.keys_b;
+
+    int which = 0;
+    fwd.q_idx = L.st.cur_u[which];
+    FNN_TRY(launch_search(fwd, batch, compute, L.maps.dp, s));  // V^0 = NN_2(U^0)
+    if (opts->max_iter == 0) {
+        FNN_TRY(launch_recip_step(L.st, which, ns, batch, 0, 2, seed_i, seed_j, seed_iter, s));
+    }
+    for (int t = 0; t < opts->max_iter; ++t) {
+        const bool last = (t == opts->max_iter - 1);
+        FNN_TRY(launch_search(bwd, batch, compute, L.maps.dp, s));  // U^{t+1} = NN_1(V^t)
+        FNN_TRY(launch_recip_step(L.st, which, ns, batch, t, last ? 1 : 0, seed_i, seed_j, seed_iter, s));
+        if (last) break;
+        which ^= 1;
+        fwd.q_idx = L.st.cur_u[which];
+        FNN_TRY(launch_search(fwd, batch, compute, L.maps.dp, s));  // V^{t+1} = NN_2(U^{t+1})
+    }
+    FNN_TRY(launch_recip_dedup(L.st, ns, batch, seed_i, seed_j, seed_iter, pairs, n_pairs, s));
+    return FNN_OK;
+}
+
+int32_t fnn_mutual_dense(int32_t batch, const fnn_map* d1, const fnn_map* d2, const fnn_opts* opts, int32_t* nn12,
+                         float* s12, int32_t* nn21, float* s21, int32_t* pairs, int32_t* n_pairs, void* workspace,
+                         size_t workspace_bytes, void* stream) {
+    if (batch < 1 || batch > FNN_MAX_BATCH) return FNN_E_SHAPE;
+    int32_t st = check_maps(batch, d1);
+    if (st != FNN_OK) return st;
+    st = check_maps(batch, d2);
+    if (st != FNN_OK) return st;
+    st = check_opts(opts);
+    if (st != FNN_OK) return st;
+    const int64_t n = d1[0].n, m = d2[0].n;
+    const int32_t d = d1[0].d;
+    if (d2[0].d != d) return FNN_E_SHAPE;
+    if (!n_pairs) return FNN_E_NULL;
+    if ((n > 0 && !nn12) || (m > 0 && !nn21)) return FNN_E_NULL;
+    if (n > 0 && m > 0 && !pairs) return FNN_E_NULL;
+
+    Carver cv{(char*)workspace, 0};
+    DenseLayout L = carve_dense(cv, batch, n, m, d, opts->compute);
+    st = check_workspace(workspace, workspace_bytes, cv.used);
+    if (st != FNN_OK) return st;
+    hipStream_t s = (hipStream_t)stream;
+
+    if (n > 0 && m > 0) FNN_TRY(prep_both(batch, d1, d2, L.maps, d, opts->compute, s));
+    FNN_TRY(launch_fill_u64(L.row_keys, (int64_t)batch * (n + m), 0, s));
+
+    DenseArgs da;
+    memset(&da, 0, sizeof(da));
+    da.d1 = (const char*)L.maps.p1;
+    da.d1_bstride = L.maps.bstride1;
+    da.d2 = (const char*)L.maps.p2;
+    da.d2_bstride = L.maps.bstride2;
+    da.n = (int32_t)n;
+    da.m = (int32_t)m;
+    da.n_blocks = (int32_t)(L.maps.n_pad / 32);
+    da.m_tiles = (int32_t)(L.maps.m_pad / 32);
+    da.row_keys = L.row_keys;
+    da.col_keys = L.col_keys;
+    // workgroup tile: up to 4096 queries (32 KB of LDS keys) x enough candidate groups that
+    // the merges into the global key tables stay rare, while small problems still spread
+    // over the whole chip
+    da.q_per_wg = (int32_t)(L.maps.n_pad < 4096 ? L.maps.n_pad : 4096);
+    if (da.q_per_wg < 32) da.q_per_wg = 32;
+    const int64_t q_wgs = (L.maps.n_pad + da.q_per_wg - 1) / da.q_per_wg;
+    const int64_t groups_total = (da.m_tiles + DENSE_TILES_PER_GROUP - 1) / DENSE_TILES_PER_GROUP;
+    int64_t groups_per_wg = 16;
+    while (groups_per_wg > 1 && q_wgs * ((groups_total + groups_per_wg - 1) / groups_per_wg) * batch < 2048) groups_per_wg >>= 1;
+    da.groups_per_wg = (int32_t)groups_per_wg;
+    FNN_TRY(launch_dense(da, batch, opts->compute, L.maps.dp, s));
+
+    DenseFinalArgs fa;
+    fa.row_keys = L.row_keys;
+    fa.col_keys = L.col_keys;
+    fa.n = (int32_t)n;
+    fa.m = (int32_t)m;
+    fa.nn12 = nn12;
+    fa.s12 = s12;
+    fa.nn21 = nn21;
+    fa.s21 = s21;
+    fa.pairs = pairs;
+    fa.n_pairs = n_pairs;
+    fa.block_counts = L.block_counts;
+    FNN_TRY(launch_dense_final(fa, batch, s));
+    if (n == 0 && m == 0) {
+        // no kernel ran: n_pairs still has to be defined
+        FNN_TRY(launch_recip_dedup(RecipState{}, 0, batch, nullptr, nullptr, nullptr, pairs, n_pairs, s));
+    }
+    return FNN_OK;
+}
+
+}  // extern "C"
+#pragma GCC visibility pop

@@ -1,0 +1,119 @@
+// Host-side declarations of the kernel launchers that the C entry points are built from.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "../../include/fnn.h"
+
+namespace fnn {
+
+typedef unsigned long long u64;
+
+// Padded channel count of a prepared map: 16-bit formats use one or two K=16 matrix
+// instructions, fp32 uses K=2 instructions on channel pairs.
+inline int padded_d(int d, int compute) {
+    if (compute == FNN_F32) return (d + 7) / 8 * 8;
+    return d <= 16 ? 16 : 32;
+}
+inline int elem_size(int dtype) { return dtype == FNN_F32 ? 4 : 2; }
+inline int64_t round_up(int64_t x, int64_t a) { return (x + a - 1) / a * a; }
+
+// ---- prepare: convert / pad the caller's maps into the workspace ------------------------
+struct PrepSide {
+    const void* src[FNN_MAX_BATCH];  // device pointers, one per pair
+    int64_t n;                       // valid pixels
+    int64_t n_pad;                   // rows written per pair (multiple of 32; rows >= n are zero)
+    int64_t row_stride;              // source row stride, elements
+    int32_t dtype;                   // source storage format
+    void* dst;                       // [batch][n_pad][dp] in the compute format
+};
+struct PrepArgs {
+    PrepSide side[2];
+    int32_t n_sides;  // 1 or 2
+    int32_t batch;
+    int32_t d;
+    int32_t dp;
+    int32_t compute;
+};
+hipError_t launch_prep(const PrepArgs& a, hipStream_t s);
+hipError_t launch_fill_u64(u64* p, int64_t count, u64 value, hipStream_t s);
+
+// ---- one-directional search ------------------------------------------------------------
+struct SearchArgs {
+    const char* src;        // prepared map the queries are rows of, [batch][*][dp]
+    int64_t src_bstride;    // bytes per pair
+    int32_t src_rows;       // rows per pair in src (row indices are clamped to it)
+    const int32_t* q_idx;   // [batch][nq] rows of src, or NULL
+    const u64* q_keys;      // [batch][nq] keys whose index field names the row, or NULL
+    const int32_t* nq_active;  // [batch] or NULL
+    int32_t nq;
+    const char* tgt;        // prepared candidate map [batch][m_tiles*32][dp]
+    int64_t tgt_bstride;
+    int32_t m;              // valid candidates
+    int32_t m_tiles;
+    u64* out_keys;          // [batch][nq], must hold 0 (or earlier partial results)
+};
+hipError_t launch_search(const SearchArgs& a, int batch, int compute, int dp, hipStream_t s);
+
+struct DecodeArgs {
+    const u64* keys;
+    const int32_t* nq_active;
+    int32_t nq;
+    int32_t* out_idx;
+    float* out_score;  // may be NULL
+};
+hipError_t launch_decode(const DecodeArgs& a, int batch, hipStream_t s);
+
+// ---- reciprocal iteration bookkeeping ----------------------------------------------------
+struct RecipState {
+    int32_t* cur_u[2];   // [batch][n_seeds] ping-pong: U^t of the seeds still moving
+    int32_t* seed_id[2]; // [batch][n_seeds] which seed sits in each slot
+    int32_t* n_active;   // [batch]
+    u64* keys_f;         // [batch][n_seeds] result of the search into image 2 (V^t)
+    u64* keys_b;         // [batch][n_seeds] result of the search back into image 1 (U^{t+1})
+    u64* sort_buf;       // [batch][sort_len] scratch for the final sort when it exceeds LDS
+    int64_t sort_len;
+};
+hipError_t launch_recip_init(const RecipState& st, const int32_t* seeds, int32_t n_seeds, int batch, hipStream_t s);
+// mode 0: ordinary iteration t; 1: last iteration (survivors are reported as unconverged);
+// 2: no iteration at all (max_iter == 0): every seed is reported unconverged with (U^0, V^0).
+hipError_t launch_recip_step(const RecipState& st, int which, int32_t n_seeds, int batch, int t, int mode,
+                             int32_t* seed_i, int32_t* seed_j, int32_t* seed_iter, hipStream_t s);
+hipError_t launch_recip_dedup(const RecipState& st, int32_t n_seeds, int batch,
+                              const int32_t* seed_i, const int32_t* seed_j, const int32_t* seed_iter,
+                              int32_t* pairs, int32_t* n_pairs, hipStream_t s);
+
+// ---- dense mutual nearest neighbours -----------------------------------------------------
+struct DenseArgs {
+    const char* d1;        // prepared queries [batch][n_pad][dp]
+    int64_t d1_bstride;
+    const char* d2;        // prepared candidates [batch][m_pad][dp]
+    int64_t d2_bstride;
+    int32_t n, m;
+    int32_t n_blocks, m_tiles;  // 32-pixel blocks per side
+    u64* row_keys;         // [batch][n] zero-initialised
+    u64* col_keys;         // [batch][m] zero-initialised
+    int32_t q_per_wg;      // queries per workgroup (multiple of 32)
+    int32_t groups_per_wg; // candidate groups (of 4 waves x J tiles) per workgroup
+};
+constexpr int DENSE_J = 2;      // candidate tiles resident per wave
+constexpr int DENSE_WAVES = 4;  // waves per workgroup
+constexpr int DENSE_TILES_PER_GROUP = DENSE_J * DENSE_WAVES;
+hipError_t launch_dense(const DenseArgs& a, int batch, int compute, int dp, hipStream_t s);
+
+struct DenseFinalArgs {
+    const u64* row_keys;
+    const u64* col_keys;
+    int32_t n, m;
+    int32_t* nn12;
+    float* s12;   // may be NULL
+    int32_t* nn21;
+    float* s21;   // may be NULL
+    int32_t* pairs;       // [batch][min(n,m)][2]
+    int32_t* n_pairs;     // [batch]
+    int32_t* block_counts;  // [batch][ceil(max(n,m)/1024)] scratch
+};
+hipError_t launch_dense_final(const DenseFinalArgs& a, int batch, hipStream_t s);
+
+}  // namespace fnn

@@ -1,0 +1,96 @@
+// Prepare step: copy the caller's descriptor maps into the workspace in the format the
+// matrix instructions consume -- the compute format of Algorithm 3 ("HybridCast": inputs
+// rounded to 16 bits, round-to-nearest-even) or plain fp32 -- with the channel count zero
+// padded to the instruction's K and the pixel count zero padded to whole 32-pixel tiles.
+#include "fnn_device.hpp"
+#include "fnn_kernels.hpp"
+
+namespace fnn {
+
+__device__ __forceinline__ float load_as_float(const void* base, int64_t idx, int dtype) {
+    if (dtype == FNN_F32) return reinterpret_cast<const float*>(base)[idx];
+    const uint16_t raw = reinterpret_cast<const uint16_t*>(base)[idx];
+    if (dtype == FNN_F16) {
+        return (float)__builtin_bit_cast(_Float16, raw);
+    }
+    return __uint_as_float((uint32_t)raw << 16);
+}
+
+__device__ __forceinline__ uint16_t float_to_bf16_rne(float f) {
+    uint32_t u = __float_as_uint(f);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+
+__device__ __forceinline__ uint16_t float_to_f16_rne(float f) {
+    _Float16 hf = (_Float16)f;  // v_cvt_f16_f32 rounds to nearest even
+    return __builtin_bit_cast(uint16_t, hf);
+}
+
+// One thread produces 8 consecutive channels of one output row.
+__global__ __launch_bounds__(256) void prep_kernel(PrepArgs a) {
+    const int side_idx = blockIdx.y / a.batch;
+    const int b = blockIdx.y % a.batch;
+    const PrepSide& sd = a.side[side_idx];
+    const int groups = a.dp / 8;
+    const int64_t total = sd.n_pad * groups;
+    const int esize = (a.compute == FNN_F32) ? 4 : 2;
+    char* dst = reinterpret_cast<char*>(sd.dst) + (int64_t)b * sd.n_pad * a.dp * esize;
+    const void* src = sd.src[b];
+    for (int64_t item = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; item < total;
+         item += (int64_t)gridDim.x * blockDim.x) {
+        const int64_t row = item / groups;
+        const int g = (int)(item % groups);
+        float v[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const int k = g * 8 + e;
+            v[e] = (row < sd.n && k < a.d) ? load_as_float(src, row * sd.row_stride + k, sd.dtype) : 0.0f;
+        }
+        if (a.compute == FNN_F32) {
+            float4* out = reinterpret_cast<float4*>(dst + (row * a.dp + g * 8) * 4);
+            out[0] = make_float4(v[0], v[1], v[2], v[3]);
+            out[1] = make_float4(v[4], v[5], v[6], v[7]);
+        } else {
+            uint16_t hbits[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+                hbits[e] = (a.compute == FNN_F16) ? float_to_f16_rne(v[e]) : float_to_bf16_rne(v[e]);
+            uint4 packed;
+            packed.x = hbits[0] | ((uint32_t)hbits[1] << 16);
+            packed.y = hbits[2] | ((uint32_t)hbits[3] << 16);
+            packed.z = hbits[4] | ((uint32_t)hbits[5] << 16);
+            packed.w = hbits[6] | ((uint32_t)hbits[7] << 16);
+            *reinterpret_cast<uint4*>(dst + (row * a.dp + g * 8) * 2) = packed;
+        }
+    }
+}
+
+__global__ __launch_bounds__(256) void fill_u64_kernel(u64* p, int64_t count, u64 value) {
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < count; i += (int64_t)gridDim.x * blockDim.x)
+        p[i] = value;
+}
+
+hipError_t launch_prep(const PrepArgs& a, hipStream_t s) {
+    int64_t most = 0;
+    for (int i = 0; i < a.n_sides; ++i) {
+        const int64_t items = a.side[i].n_pad * (a.dp / 8);
+        if (items > most) most = items;
+    }
+    if (most == 0) return hipSuccess;
+    int64_t blocks = (most + 255) / 256;
+    if (blocks > 4096) blocks = 4096;
+    dim3 grid((unsigned)blocks, (unsigned)(a.n_sides * a.batch));
+    hipLaunchKernelGGL(prep_kernel, grid, dim3(256), 0, s, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_fill_u64(u64* p, int64_t count, u64 value, hipStream_t s) {
+    if (count <= 0) return hipSuccess;
+    int64_t blocks = (count + 255) / 256;
+    if (blocks > 2048) blocks = 2048;
+    hipLaunchKernelGGL(fill_u64_kernel, dim3((unsigned)blocks), dim3(256), 0, s, p, count, value);
+    return hipGetLastError();
+}
+
+}  // namespace fnn
