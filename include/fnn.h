@@ -27,8 +27,8 @@
  *  - `batch` independent image pairs share shapes; maps are passed as HOST arrays of
  *    `batch` fnn_map structs (1 <= batch <= FNN_MAX_BATCH); every other array is ONE
  *    contiguous DEVICE buffer with the batch index outermost.
- *  - The caller owns every buffer.  The library allocates nothing, keeps no state between
- *    calls and touches only the outputs and `workspace` (device, >= fnn_workspace_bytes(),
+ *  - The caller owns every buffer.  The library allocates no device memory, keeps no state
+ *    between calls (but see fnn_trace_begin) and touches only the outputs and `workspace` (device, >= fnn_workspace_bytes(),
  *    256-byte aligned).  All work is enqueued on `stream` (a hipStream_t, NULL = default
  *    stream) and the call returns without waiting; outputs are valid once the stream has
  *    reached that point.  Two calls that share a workspace must be ordered by the stream.
@@ -140,6 +140,20 @@ int32_t fnn_mutual_dense(int32_t batch, const fnn_map* d1, const fnn_map* d2, co
                          int32_t* nn12, float* s12, int32_t* nn21, float* s21,
                          int32_t* pairs, int32_t* n_pairs,
                          void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Measurement aid (not part of the paper's method; used by the benchmark).  Between
+ * fnn_trace_begin and fnn_trace_end every kernel the library launches -- up to max_kernels,
+ * later ones run untimed -- carries its own pair of HIP events, so that fnn_trace_end can
+ * report each kernel's device-side duration.  fnn_trace_end waits for the traced kernels,
+ * writes min(*n_recorded, capacity) entries (kinds[i] names the kernel, see
+ * fnn_trace_kind_name; milliseconds[i] is its duration, in launch order) to HOST arrays and
+ * closes the trace.  This is the only state the library holds; it is process-wide and not
+ * thread-safe, and a trace must not be open during HIP graph capture.
+ */
+int32_t fnn_trace_begin(int32_t max_kernels);
+int32_t fnn_trace_end(int32_t capacity, int32_t* kinds, float* milliseconds, int32_t* n_recorded);
+const char* fnn_trace_kind_name(int32_t kind);
 
 #ifdef __cplusplus
 }

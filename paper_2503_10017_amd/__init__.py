@@ -13,6 +13,8 @@ from .binding import (  # noqa: F401
     fnn_nearest,
     fnn_reciprocal,
     fnn_status_string,
+    fnn_trace_begin,
+    fnn_trace_end,
     fnn_workspace_bytes,
     library_path,
     load_library,

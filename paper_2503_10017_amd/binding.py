@@ -60,6 +60,12 @@ def load_library():
     lib.fnn_reciprocal.argtypes = [i32, vp, vp, vp, i64, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.fnn_mutual_dense.restype = i32
     lib.fnn_mutual_dense.argtypes = [i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.fnn_trace_begin.restype = i32
+    lib.fnn_trace_begin.argtypes = [i32]
+    lib.fnn_trace_end.restype = i32
+    lib.fnn_trace_end.argtypes = [i32, vp, vp, vp]
+    lib.fnn_trace_kind_name.restype = ctypes.c_char_p
+    lib.fnn_trace_kind_name.argtypes = [i32]
     _lib = lib
     return lib
 
@@ -217,3 +223,22 @@ def fnn_mutual_dense(d1: MapsLike, d2: MapsLike, compute="f16", out: Optional[di
     if st != 0:
         raise FnnError(st, "fnn_mutual_dense")
     return out
+
+
+def fnn_trace_begin(max_kernels: int = 4096) -> None:
+    st = load_library().fnn_trace_begin(int(max_kernels))
+    if st != 0:
+        raise FnnError(st, "fnn_trace_begin")
+
+
+def fnn_trace_end(capacity: int = 4096):
+    """Returns a list of (kernel name, milliseconds) in launch order and closes the trace."""
+    lib = load_library()
+    kinds = (ctypes.c_int32 * capacity)()
+    ms = (ctypes.c_float * capacity)()
+    n = ctypes.c_int32(0)
+    st = lib.fnn_trace_end(capacity, kinds, ms, ctypes.byref(n))
+    if st != 0:
+        raise FnnError(st, "fnn_trace_end")
+    count = min(int(n.value), capacity)
+    return [(lib.fnn_trace_kind_name(kinds[i]).decode(), float(ms[i])) for i in range(count)]

@@ -11,6 +11,7 @@
 // All merges are 64-bit max operations on (score, inverted index) keys.
 #include "fnn_device.hpp"
 #include "fnn_kernels.hpp"
+#include "trace.hpp"
 
 namespace fnn {
 
@@ -219,9 +220,8 @@ template <int CT, int DP>
 static hipError_t launch_dense_t(const DenseArgs& a, int batch, hipStream_t s) {
     const int tiles_per_wg = a.groups_per_wg * DENSE_WAVES * DENSE_J;
     dim3 grid((a.m_tiles + tiles_per_wg - 1) / tiles_per_wg, (a.n_blocks * 32 + a.q_per_wg - 1) / a.q_per_wg, batch);
-    hipLaunchKernelGGL((dense_kernel<CT, DP, DENSE_J>), grid, dim3(DENSE_WAVES * 64),
-                       (size_t)a.q_per_wg * sizeof(u64), s, a);
-    return hipGetLastError();
+    return launch(TK_DENSE, dense_kernel<CT, DP, DENSE_J>, grid, dim3(DENSE_WAVES * 64),
+                  (size_t)a.q_per_wg * sizeof(u64), s, a);
 }
 
 hipError_t launch_dense(const DenseArgs& a, int batch, int compute, int dp, hipStream_t s) {
@@ -245,14 +245,11 @@ hipError_t launch_dense_final(const DenseFinalArgs& a, int batch, hipStream_t s)
     const int most = a.n > a.m ? a.n : a.m;
     const int blocks = (most + FINAL_THREADS - 1) / FINAL_THREADS;
     if (blocks == 0 || batch <= 0) return hipSuccess;
-    hipLaunchKernelGGL(dense_decode_kernel, dim3(blocks, batch), dim3(FINAL_THREADS), 0, s, a, blocks);
-    hipError_t e = hipGetLastError();
+    hipError_t e = launch(TK_DENSE_FINAL, dense_decode_kernel, dim3(blocks, batch), dim3(FINAL_THREADS), 0, s, a, blocks);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(dense_scan_kernel, dim3(batch), dim3(FINAL_THREADS), 0, s, a, blocks);
-    e = hipGetLastError();
+    e = launch(TK_DENSE_FINAL, dense_scan_kernel, dim3(batch), dim3(FINAL_THREADS), 0, s, a, blocks);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(dense_scatter_kernel, dim3(blocks, batch), dim3(FINAL_THREADS), 0, s, a, blocks);
-    return hipGetLastError();
+    return launch(TK_DENSE_FINAL, dense_scatter_kernel, dim3(blocks, batch), dim3(FINAL_THREADS), 0, s, a, blocks);
 }
 
 }  // namespace fnn

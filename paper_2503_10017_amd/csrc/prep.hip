@@ -4,6 +4,7 @@
 // padded to the instruction's K and the pixel count zero padded to whole 32-pixel tiles.
 #include "fnn_device.hpp"
 #include "fnn_kernels.hpp"
+#include "trace.hpp"
 
 namespace fnn {
 
@@ -81,16 +82,14 @@ hipError_t launch_prep(const PrepArgs& a, hipStream_t s) {
     int64_t blocks = (most + 255) / 256;
     if (blocks > 4096) blocks = 4096;
     dim3 grid((unsigned)blocks, (unsigned)(a.n_sides * a.batch));
-    hipLaunchKernelGGL(prep_kernel, grid, dim3(256), 0, s, a);
-    return hipGetLastError();
+    return launch(TK_PREP, prep_kernel, grid, dim3(256), 0, s, a);
 }
 
 hipError_t launch_fill_u64(u64* p, int64_t count, u64 value, hipStream_t s) {
     if (count <= 0) return hipSuccess;
     int64_t blocks = (count + 255) / 256;
     if (blocks > 2048) blocks = 2048;
-    hipLaunchKernelGGL(fill_u64_kernel, dim3((unsigned)blocks), dim3(256), 0, s, p, count, value);
-    return hipGetLastError();
+    return launch(TK_FILL, fill_u64_kernel, dim3((unsigned)blocks), dim3(256), 0, s, p, count, value);
 }
 
 }  // namespace fnn

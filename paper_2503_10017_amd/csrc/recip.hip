@@ -5,6 +5,7 @@
 // never reads a count back.
 #include "fnn_device.hpp"
 #include "fnn_kernels.hpp"
+#include "trace.hpp"
 
 namespace fnn {
 
@@ -156,8 +157,7 @@ hipError_t launch_recip_init(const RecipState& st, const int32_t* seeds, int32_t
     int blocks = (n_seeds + 255) / 256;
     if (blocks < 1) blocks = 1;
     if (blocks > 256) blocks = 256;
-    hipLaunchKernelGGL(recip_init_kernel, dim3(blocks, batch), dim3(256), 0, s, st, seeds, n_seeds);
-    return hipGetLastError();
+    return launch(TK_RECIP_INIT, recip_init_kernel, dim3(blocks, batch), dim3(256), 0, s, st, seeds, n_seeds);
 }
 
 hipError_t launch_recip_step(const RecipState& st, int which, int32_t n_seeds, int batch, int t, int mode,
@@ -176,8 +176,7 @@ hipError_t launch_recip_step(const RecipState& st, int which, int32_t n_seeds, i
     a.seed_i = seed_i;
     a.seed_j = seed_j;
     a.seed_iter = seed_iter;
-    hipLaunchKernelGGL(recip_step_kernel, dim3(batch), dim3(STEP_THREADS), 0, s, a);
-    return hipGetLastError();
+    return launch(TK_RECIP_STEP, recip_step_kernel, dim3(batch), dim3(STEP_THREADS), 0, s, a);
 }
 
 hipError_t launch_recip_dedup(const RecipState& st, int32_t n_seeds, int batch,
@@ -194,8 +193,7 @@ hipError_t launch_recip_dedup(const RecipState& st, int32_t n_seeds, int batch,
     const size_t lds_bytes = (size_t)st.sort_len * sizeof(u64);
     const bool in_lds = lds_bytes <= 48 * 1024;
     a.global_buf = in_lds ? nullptr : st.sort_buf;
-    hipLaunchKernelGGL(recip_dedup_kernel, dim3(batch), dim3(STEP_THREADS), in_lds ? lds_bytes : 0, s, a);
-    return hipGetLastError();
+    return launch(TK_RECIP_DEDUP, recip_dedup_kernel, dim3(batch), dim3(STEP_THREADS), in_lds ? lds_bytes : 0, s, a);
 }
 
 }  // namespace fnn

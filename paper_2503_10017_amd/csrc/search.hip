@@ -11,6 +11,7 @@
 // keys with a 64-bit atomic max (score first, lowest index on ties).
 #include "fnn_device.hpp"
 #include "fnn_kernels.hpp"
+#include "trace.hpp"
 
 namespace fnn {
 
@@ -133,8 +134,7 @@ static hipError_t launch_search_t(const SearchArgs& a, int batch, hipStream_t s)
                               ((a.m_tiles + SEARCH_MIN_TILES - 1) / SEARCH_MIN_TILES);
     const int64_t need = (max_units + SEARCH_WAVES - 1) / SEARCH_WAVES;
     if (need < wgs) wgs = (int)(need > 0 ? need : 1);
-    hipLaunchKernelGGL((search_kernel<CT, DP, SEARCH_R>), dim3(wgs, batch), dim3(SEARCH_WAVES * 64), 0, s, a);
-    return hipGetLastError();
+    return launch(TK_SEARCH, search_kernel<CT, DP, SEARCH_R>, dim3(wgs, batch), dim3(SEARCH_WAVES * 64), 0, s, a);
 }
 
 hipError_t launch_search(const SearchArgs& a, int batch, int compute, int dp, hipStream_t s) {
@@ -158,8 +158,7 @@ hipError_t launch_decode(const DecodeArgs& a, int batch, hipStream_t s) {
     if (a.nq <= 0 || batch <= 0) return hipSuccess;
     int blocks = (a.nq + 255) / 256;
     if (blocks > 1024) blocks = 1024;
-    hipLaunchKernelGGL(decode_kernel, dim3(blocks, batch), dim3(256), 0, s, a);
-    return hipGetLastError();
+    return launch(TK_DECODE, decode_kernel, dim3(blocks, batch), dim3(256), 0, s, a);
 }
 
 }  // namespace fnn

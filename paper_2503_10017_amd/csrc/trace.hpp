@@ -1,0 +1,37 @@
+// Optional per-kernel timing: when a trace is open every kernel launch of the library is
+// bracketed by a pair of HIP events attached to the dispatch itself, so the elapsed time of
+// a pair is that kernel's own duration.  Closed (the default), launches are plain.
+#pragma once
+#include <hip/hip_ext.h>
+#include <hip/hip_runtime.h>
+
+namespace fnn {
+
+enum TraceKind : int {
+    TK_PREP = 0,
+    TK_FILL = 1,
+    TK_SEARCH = 2,
+    TK_DECODE = 3,
+    TK_RECIP_INIT = 4,
+    TK_RECIP_STEP = 5,
+    TK_RECIP_DEDUP = 6,
+    TK_DENSE = 7,
+    TK_DENSE_FINAL = 8,
+    TK_COUNT = 9
+};
+
+// Returns false when no trace is open or it is full; otherwise hands out the next event pair.
+bool trace_next(int kind, hipEvent_t* start, hipEvent_t* stop);
+
+template <typename Kernel, typename... Args>
+inline hipError_t launch(int kind, Kernel kernel, dim3 grid, dim3 block, size_t lds_bytes, hipStream_t s, Args... args) {
+    hipEvent_t e0, e1;
+    if (trace_next(kind, &e0, &e1)) {
+        hipExtLaunchKernelGGL(kernel, grid, block, lds_bytes, s, e0, e1, 0, args...);
+    } else {
+        hipLaunchKernelGGL(kernel, grid, block, lds_bytes, s, args...);
+    }
+    return hipGetLastError();
+}
+
+}  // namespace fnn

@@ -1,0 +1,123 @@
+"""Shared pieces of the GPU parity tests (which call the HIP library through its C ABI)."""
+import numpy as np
+import torch
+
+import oracle
+import paper_2503_10017_amd as fnn
+
+DEV = torch.device("cuda:0")
+
+# Index parity thresholds on Gaussian workloads: the GPU must return the oracle's index
+# wherever the oracle's top-1/top-2 gap exceeds this (16-bit compute: input rounding moves
+# a unit-vector score by up to ~5e-4 (fp16) / a few e-3 (bf16, compared on rounded inputs
+# instead); fp32 compute differs from the oracle only by summation order).
+GAP_HALF = 1e-3
+GAP_F32 = 1e-5
+SCORE_TOL = 1e-3
+# against the oracle run on inputs rounded the same way, only fp32 summation order differs
+GAP_ROUNDED = 2e-5
+SCORE_TOL_ROUNDED = 4e-6
+
+ROUNDERS = {"f16": oracle.round_fp16, "bf16": oracle.round_bf16, "f32": lambda x: x}
+
+
+def dev(x):
+    return torch.from_numpy(np.ascontiguousarray(x)).to(DEV)
+
+
+def host(t):
+    return t.detach().cpu().numpy()
+
+
+def exact_maps(seed, n, m, d):
+    rng = np.random.default_rng(seed)
+    a = rng.integers(-8, 9, size=(n, d)).astype(np.float32) / 8
+    b = rng.integers(-8, 9, size=(m, d)).astype(np.float32) / 8
+    return a, b
+
+
+def unit_maps(seed, n, m, d):
+    rng = np.random.default_rng(seed)
+    a = rng.standard_normal((n, d))
+    b = rng.standard_normal((m, d))
+    a /= np.linalg.norm(a, axis=1, keepdims=True)
+    b /= np.linalg.norm(b, axis=1, keepdims=True)
+    return a.astype(np.float32), b.astype(np.float32)
+
+
+def check_nearest_against(gpu_idx, gpu_score, ref_idx, ref_best, ref_second, gap_thr, score_tol, what=""):
+    clear = (ref_best - ref_second) > gap_thr
+    bad = clear & (gpu_idx != ref_idx)
+    assert not bad.any(), f"{what}: {bad.sum()} indices differ where the gap is clear (first {np.nonzero(bad)[0][:5]})"
+    assert np.all(np.abs(gpu_score - ref_best) <= score_tol), \
+        f"{what}: max score error {np.abs(gpu_score - ref_best).max()}"
+    return clear
+
+
+def check_nearest_gaussian(a, b, compute, gpu_idx, gpu_score, what=""):
+    """Both comparisons: vs the oracle on the caller's fp32 data (the stated tolerance) and vs
+    the oracle on data rounded like the GPU path rounds it (tight)."""
+    ri, rb, rs = oracle.nearest(a, b)
+    if compute == "bf16":
+        # bf16 rounding moves scores by more than 1e-3: only the rounded-input comparison binds
+        pass
+    else:
+        thr = GAP_F32 if compute == "f32" else GAP_HALF
+        check_nearest_against(gpu_idx, gpu_score, ri, rb, rs, thr, SCORE_TOL, what + " (fp32 inputs)")
+    rnd = ROUNDERS[compute]
+    ri, rb, rs = oracle.nearest(rnd(a), rnd(b))
+    clear = check_nearest_against(gpu_idx, gpu_score, ri, rb, rs, GAP_ROUNDED, SCORE_TOL_ROUNDED,
+                                  what + " (rounded inputs)")
+    return clear
+
+
+def run_reciprocal(d1, d2, seeds, max_iter, compute):
+    """Batched call through the C ABI; d1/d2 lists of [n][d] arrays, seeds [batch][n_seeds]."""
+    t1 = [dev(x) for x in d1]
+    t2 = [dev(x) for x in d2]
+    out = fnn.fnn_reciprocal(t1, t2, dev(np.asarray(seeds, dtype=np.int32)), max_iter=max_iter, compute=compute)
+    torch.cuda.synchronize()
+    return {k: host(v) for k, v in out.items()}
+
+
+def check_reciprocal_exact(got, b, ref):
+    n_pairs = int(got["n_pairs"][b])
+    assert np.array_equal(got["seed_i"][b], ref["seed_i"])
+    assert np.array_equal(got["seed_j"][b], ref["seed_j"])
+    assert np.array_equal(got["seed_iter"][b], ref["seed_iter"])
+    assert np.array_equal(got["pairs"][b, :n_pairs], ref["pairs"])
+    assert np.all(got["pairs"][b, n_pairs:] == -1)
+
+
+def check_reciprocal_pinned(got, b, ref, d1, d2, gap_thr, what=""):
+    """Seeds whose whole oracle walk had clear gaps must match exactly; the rest must still be
+    consistent: the pair list is exactly the sorted set of the converged seeds' pairs, and
+    every returned pair is mutually nearest up to the gap threshold."""
+    gi, gj, gt = got["seed_i"][b], got["seed_j"][b], got["seed_iter"][b]
+    pinned = ref["min_gap"] > gap_thr
+    assert pinned.mean() > 0.5, f"{what}: only {pinned.mean():.2f} of the seeds are pinned"
+    for name, g, r in (("seed_i", gi, ref["seed_i"]), ("seed_j", gj, ref["seed_j"]), ("seed_iter", gt, ref["seed_iter"])):
+        bad = pinned & (g != r)
+        assert not bad.any(), f"{what}: {name} differs for {bad.sum()} pinned seeds (first {np.nonzero(bad)[0][:5]})"
+    n_pairs = int(got["n_pairs"][b])
+    done = gt >= 0
+    want_pairs = np.unique(np.stack([gi[done], gj[done]], axis=1), axis=0) if done.any() else np.zeros((0, 2), np.int32)
+    assert np.array_equal(got["pairs"][b, :n_pairs], want_pairs), f"{what}: pair list is not the set of converged seeds"
+    assert np.all(got["pairs"][b, n_pairs:] == -1)
+    # pairs of pinned seeds are in the list; extra pairs trace back to unpinned seeds
+    got_set = set(map(tuple, want_pairs.tolist()))
+    pinned_pairs = set(zip(ref["seed_i"][pinned & (ref["seed_iter"] >= 0)].tolist(),
+                           ref["seed_j"][pinned & (ref["seed_iter"] >= 0)].tolist()))
+    assert pinned_pairs <= got_set
+    extra = got_set - set(map(tuple, ref["pairs"].tolist()))
+    unpinned_pairs = set(zip(gi[~pinned & done].tolist(), gj[~pinned & done].tolist()))
+    assert extra <= unpinned_pairs, f"{what}: {len(extra - unpinned_pairs)} unexplained pairs"
+    # near-mutuality of what unpinned seeds returned (checked with the oracle's arithmetic)
+    loose = np.nonzero(~pinned & done)[0]
+    if loose.size:
+        i, j = gi[loose], gj[loose]
+        _, best_i, _ = oracle.nearest(d1[i], d2)
+        _, best_j, _ = oracle.nearest(d2[j], d1)
+        s = np.einsum("nd,nd->n", d1[i].astype(np.float64), d2[j].astype(np.float64))
+        assert np.all(s >= best_i - 2 * gap_thr - 1e-6) and np.all(s >= best_j - 2 * gap_thr - 1e-6), what
+    return pinned

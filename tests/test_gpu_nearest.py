@@ -1,0 +1,109 @@
+"""fnn_nearest on the GPU against the CPU oracle (element by element)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2503_10017_amd as fnn
+from gpu_helpers import DEV, check_nearest_gaussian, dev, exact_maps, host, unit_maps
+
+pytestmark = pytest.mark.gpu
+
+COMPUTES = ["f16", "bf16", "f32"]
+
+
+@pytest.mark.parametrize("compute", COMPUTES)
+@pytest.mark.parametrize("k,m,d", [(1, 1, 1), (1, 70, 24), (5, 40, 24), (63, 31, 24), (64, 32, 16), (65, 33, 8),
+                                   (127, 129, 17), (128, 128, 32), (129, 1000, 24), (200, 4097, 3),
+                                   (3072, 3072, 24), (1000, 20011, 24)])
+def test_exact_inputs_bit_exact(compute, k, m, d):
+    a, b = exact_maps(1000 * k + m + d, k, m, d)
+    ri, rb, _ = oracle.nearest(a, b)
+    gi, gs = fnn.fnn_nearest(dev(a), dev(b), compute=compute)
+    torch.cuda.synchronize()
+    assert np.array_equal(host(gi)[0], ri)
+    assert np.array_equal(host(gs)[0], rb)
+
+
+@pytest.mark.parametrize("compute", COMPUTES)
+@pytest.mark.parametrize("k,m,d", [(300, 5000, 24), (1000, 40000, 24), (77, 3333, 32), (500, 9000, 12)])
+def test_gaussian_inputs(compute, k, m, d):
+    a, b = unit_maps(7 * k + m, k, m, d)
+    gi, gs = fnn.fnn_nearest(dev(a), dev(b), compute=compute)
+    torch.cuda.synchronize()
+    clear = check_nearest_gaussian(a, b, compute, host(gi)[0], host(gs)[0], f"{compute} {k}x{m}x{d}")
+    assert clear.mean() > 0.9
+
+
+@pytest.mark.parametrize("compute", ["f16", "f32"])
+def test_query_list_active_count_and_batch(compute):
+    batch, n, m, d, nq = 3, 700, 2100, 24, 333
+    rng = np.random.default_rng(5)
+    srcs, tgts = [], []
+    for b in range(batch):
+        a, t = exact_maps(50 + b, n, m, d)
+        srcs.append(a)
+        tgts.append(t)
+    q = rng.integers(0, n, size=(batch, nq)).astype(np.int32)
+    active = np.array([333, 0, 97], dtype=np.int32)
+    out_idx = torch.full((batch, nq), -7, dtype=torch.int32, device=DEV)
+    out_score = torch.full((batch, nq), -7.0, dtype=torch.float32, device=DEV)
+    fnn.fnn_nearest([dev(x) for x in srcs], [dev(x) for x in tgts], q_idx=dev(q), nq_active=dev(active),
+                    compute=compute, out_idx=out_idx, out_score=out_score)
+    torch.cuda.synchronize()
+    gi, gs = host(out_idx), host(out_score)
+    for b in range(batch):
+        k = int(active[b])
+        ri, rb, _ = oracle.nearest(srcs[b][q[b, :k]], tgts[b])
+        assert np.array_equal(gi[b, :k], ri)
+        assert np.array_equal(gs[b, :k], rb)
+        assert np.all(gi[b, k:] == -7) and np.all(gs[b, k:] == -7.0)     # untouched
+
+
+def test_storage_formats_and_row_stride():
+    # fp16 / bf16 storage, rows 40 elements apart; exactly representable values
+    n, m, d = 257, 1111, 24
+    a, b = exact_maps(9, n, m, d)
+    ri, rb, _ = oracle.nearest(a, b)
+    for dtype in (torch.float16, torch.bfloat16, torch.float32):
+        wide_a = torch.zeros((n, 40), dtype=dtype, device=DEV)
+        wide_b = torch.zeros((m, 40), dtype=dtype, device=DEV)
+        wide_a[:, :d] = dev(a).to(dtype)
+        wide_b[:, :d] = dev(b).to(dtype)
+        wide_a[:, d:] = 3.0                          # junk beyond d must be ignored
+        for compute in COMPUTES:
+            gi, gs = fnn.fnn_nearest(wide_a[:, :d], wide_b[:, :d], compute=compute)
+            torch.cuda.synchronize()
+            assert np.array_equal(host(gi)[0], ri), (dtype, compute)
+            assert np.array_equal(host(gs)[0], rb), (dtype, compute)
+
+
+def test_empty_candidates_and_queries():
+    a, b = exact_maps(3, 10, 10, 24)
+    gi, gs = fnn.fnn_nearest(dev(a), torch.zeros((0, 24), device=DEV), compute="f16")
+    torch.cuda.synchronize()
+    assert np.all(host(gi) == -1) and np.all(np.isneginf(host(gs)))
+    gi, gs = fnn.fnn_nearest(dev(a), dev(b), nq=0, compute="f16")
+    assert gi.shape == (1, 0)
+
+
+def test_negative_scores_and_ties_to_lowest_index():
+    # all scores negative; many exact ties
+    a = -np.abs(exact_maps(4, 50, 1, 24)[0]) - 0.125
+    b = np.repeat(np.abs(exact_maps(5, 7, 1, 24)[0]) + 0.125, 40, axis=0)    # each candidate 40 times
+    ri, rb, rs = oracle.nearest(a, b)
+    assert np.all(rb < 0) and np.all(rb == rs)
+    for compute in COMPUTES:
+        gi, gs = fnn.fnn_nearest(dev(a), dev(b), compute=compute)
+        torch.cuda.synchronize()
+        assert np.array_equal(host(gi)[0], ri) and np.array_equal(host(gs)[0], rb)
+    assert np.all(ri % 40 == 0)
+
+
+def test_repeated_calls_are_deterministic():
+    a, b = unit_maps(11, 2000, 30000, 24)
+    ta, tb = dev(a), dev(b)
+    first = [host(x) for x in fnn.fnn_nearest(ta, tb, compute="f16")]
+    for _ in range(3):
+        again = [host(x) for x in fnn.fnn_nearest(ta, tb, compute="f16")]
+        assert np.array_equal(first[0], again[0]) and np.array_equal(first[1], again[1])
