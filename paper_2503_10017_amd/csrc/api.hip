@@ -243,13 +243,7 @@ int32_t fnn_nearest(int32_t batch, const fnn_map* src, const int32_t* q_idx, int
     sa.m_tiles = (int32_t)(L.maps.m_pad / 32);
     sa.out_keys = L.keys;
     FNN_TRY(launch_search(sa, batch, opts->compute, L.maps.dp, s));
-    DecodeArgs da;
-    da.keys = L.keys;
-    da.nq_active = nq_active;
-    da.nq = (int32_t)nq;
-    da.out_idx = out_idx;
-    da.out_score = out_score;
-    FNN_TRY(launch_decode(da, batch, s));
+    FNN_TRY(launch_resolve(sa, batch, opts->compute, L.maps.dp, out_idx, out_score, s));
     return FNN_OK;
 }
 
@@ -317,17 +311,20 @@ int32_t fnn_reciprocal(int32_t batch, const fnn_map* d1, const fnn_map* d2, cons
     int which = 0;
     fwd.q_idx = L.st.cur_u[which];
     FNN_TRY(launch_search(fwd, batch, compute, L.maps.dp, s));  // V^0 = NN_2(U^0)
+    FNN_TRY(launch_resolve(fwd, batch, compute, L.maps.dp, nullptr, nullptr, s));
     if (opts->max_iter == 0) {
         FNN_TRY(launch_recip_step(L.st, which, ns, batch, 0, 2, seed_i, seed_j, seed_iter, s));
     }
     for (int t = 0; t < opts->max_iter; ++t) {
         const bool last = (t == opts->max_iter - 1);
         FNN_TRY(launch_search(bwd, batch, compute, L.maps.dp, s));  // U^{t+1} = NN_1(V^t)
+        FNN_TRY(launch_resolve(bwd, batch, compute, L.maps.dp, nullptr, nullptr, s));
         FNN_TRY(launch_recip_step(L.st, which, ns, batch, t, last ? 1 : 0, seed_i, seed_j, seed_iter, s));
         if (last) break;
         which ^= 1;
         fwd.q_idx = L.st.cur_u[which];
         FNN_TRY(launch_search(fwd, batch, compute, L.maps.dp, s));  // V^{t+1} = NN_2(U^{t+1})
+        FNN_TRY(launch_resolve(fwd, batch, compute, L.maps.dp, nullptr, nullptr, s));
     }
     FNN_TRY(launch_recip_dedup(L.st, ns, batch, seed_i, seed_j, seed_iter, pairs, n_pairs, s));
     return FNN_OK;

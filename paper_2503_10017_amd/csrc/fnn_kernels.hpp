@@ -54,16 +54,12 @@ struct SearchArgs {
     int32_t m_tiles;
     u64* out_keys;          // [batch][nq], must hold 0 (or earlier partial results)
 };
+// Pass 1: out_keys receive (best score, tile of 32 candidates holding it).
 hipError_t launch_search(const SearchArgs& a, int batch, int compute, int dp, hipStream_t s);
-
-struct DecodeArgs {
-    const u64* keys;
-    const int32_t* nq_active;
-    int32_t nq;
-    int32_t* out_idx;
-    float* out_score;  // may be NULL
-};
-hipError_t launch_decode(const DecodeArgs& a, int batch, hipStream_t s);
+// Pass 2: out_keys become (best score, lowest candidate index); optionally also stored to
+// out_idx / out_score (either may be NULL).  Queries without any candidate get -1 / -inf.
+hipError_t launch_resolve(const SearchArgs& a, int batch, int compute, int dp, int32_t* out_idx, float* out_score,
+                          hipStream_t s);
 
 // ---- reciprocal iteration bookkeeping ----------------------------------------------------
 struct RecipState {

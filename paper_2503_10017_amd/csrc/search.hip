@@ -5,6 +5,10 @@
 // a per-query running best, so no score ever leaves the register file and memory traffic is
 // one pass over the candidate map per resident query group.
 //
+// The search runs in two passes: pass 1 finds, per query, the best score and the tile of 32
+// candidates that holds it, at roughly 0.6 vector operations per score; pass 2 recomputes
+// that one tile per query to name the lowest candidate index attaining the score.
+//
 // Work split (decided on the device from the live query count, so the host never needs to
 // read it back): the queries form row groups of R*32, the candidate tiles are cut into
 // chunks, one wave takes one (row group, chunk) unit and merges its result into the packed
@@ -18,13 +22,43 @@ namespace fnn {
 constexpr int SEARCH_R = 4;           // 32-query blocks resident per wave
 constexpr int SEARCH_MIN_TILES = 4;   // shortest chunk worth a wave
 constexpr int SEARCH_WAVES = 4;       // waves per workgroup
+constexpr int SEARCH_P = 4;           // candidate tiles in flight per wave
 
-template <int CT, int DP, int R>
-__global__ __launch_bounds__(SEARCH_WAVES * 64) void search_kernel(SearchArgs a) {
+__device__ __forceinline__ float max3(float a, float b, float c) { return __builtin_fmaxf(__builtin_fmaxf(a, b), c); }
+
+// Largest of `seed` and the 16 scores of one result fragment: eight 3-input max operations.
+__device__ __forceinline__ float fold16(float seed, const f32x16& x) {
+    const float t0 = max3(x[0], x[1], x[2]);
+    const float t1 = max3(x[3], x[4], x[5]);
+    const float t2 = max3(x[6], x[7], x[8]);
+    const float t3 = max3(x[9], x[10], x[11]);
+    const float t4 = max3(x[12], x[13], x[14]);
+    const float t5 = max3(t0, t1, t2);
+    const float t6 = max3(t3, t4, x[15]);
+    return max3(seed, t5, t6);
+}
+
+__device__ __forceinline__ int64_t query_row(const SearchArgs& a, int64_t qbase, int slot) {
+    int64_t row;
+    if (a.q_keys) row = (int64_t)(0xFFFFFFFFu - (uint32_t)(a.q_keys[qbase + slot] & 0xFFFFFFFFull));
+    else if (a.q_idx) row = a.q_idx[qbase + slot];
+    else row = slot;
+    return min(max(row, (int64_t)0), (int64_t)a.src_rows - 1);  // never read outside the map
+}
+
+// Pass 1: per query the best score and the 32-candidate TILE that holds it.  A lane only
+// keeps a running maximum (3-input max) and, once per tile, notes the tile when the
+// maximum rose -- strictly, so the lowest tile wins among equal scores.  The key written
+// here carries the tile number in its index field; pass 2 turns it into the candidate index.
+// (waves_per_eu >= 2 caps the kernel at 256 registers, which lets the matrix instructions
+// write their results straight into ordinary vector registers.)
+template <int CT, int DP, int R, int P>
+__global__ __launch_bounds__(SEARCH_WAVES * 64) __attribute__((amdgpu_waves_per_eu(2)))
+void search_kernel(SearchArgs a) {
     using O = Ops<CT, DP>;
     using Frag = typename O::Frag;
     const int lane = threadIdx.x & 63, c = lane & 31, h = lane >> 5;
-    const int wave = blockIdx.x * SEARCH_WAVES + (threadIdx.x >> 6);
+    const int wave = blockIdx.x * SEARCH_WAVES + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int n_waves = gridDim.x * SEARCH_WAVES;
     const int b = blockIdx.y;
 
@@ -47,81 +81,118 @@ __global__ __launch_bounds__(SEARCH_WAVES * 64) void search_kernel(SearchArgs a)
         const int chunk = (int)(unit / row_groups);
         const int rg = (int)(unit % row_groups);
         const int slot0 = rg * 32 * R;
-        const int n_blk = min(R, (n_act - slot0 + 31) / 32);
 
+        // blocks past the live queries of the last row group are computed on row 0 and dropped
         Frag q[R];
         float best[R];
-        int best_j[R];
+        int best_tile[R];
 #pragma unroll
         for (int r = 0; r < R; ++r) {
             const int slot = slot0 + r * 32 + c;
-            int64_t row = 0;
-            if (slot < n_act) {
-                if (a.q_keys) row = (int64_t)(0xFFFFFFFFu - (uint32_t)(a.q_keys[qbase + slot] & 0xFFFFFFFFull));
-                else if (a.q_idx) row = a.q_idx[qbase + slot];
-                else row = slot;
-            }
-            row = min(max(row, (int64_t)0), (int64_t)a.src_rows - 1);  // never read outside the map
+            const int64_t row = slot < n_act ? query_row(a, qbase, slot) : 0;
             q[r] = O::load(src + row * O::ROW_BYTES, h);
             best[r] = ninf;
-            best_j[r] = 0x7FFFFFFF;
+            best_tile[r] = 0x7FFFFFFF;
         }
 
         const int t0 = chunk * tiles_per_chunk;
         const int t1 = min(t0 + tiles_per_chunk, a.m_tiles);
-        Frag cur = O::load(tgt + ((int64_t)t0 * 32 + c) * O::ROW_BYTES, h);
-        for (int t = t0; t < t1; ++t) {
-            Frag nxt = cur;
-            if (t + 1 < t1) nxt = O::load(tgt + ((int64_t)(t + 1) * 32 + c) * O::ROW_BYTES, h);
-            const int jbase = t * 32;
-            const bool tail = jbase + 32 > a.m;
+        // P candidate tiles are always in flight towards the registers; a slot is refilled
+        // as soon as its tile has been handed to the matrix cores
+        Frag ring[P];
 #pragma unroll
-            for (int r = 0; r < R; ++r) {
-                if (r < n_blk) {
-                    f32x16 acc = O::mma(cur, q[r]);
-                    if (tail) {
+        for (int p = 0; p < P; ++p)
+            ring[p] = O::load(tgt + ((int64_t)min(t0 + p, t1 - 1) * 32 + c) * O::ROW_BYTES, h);
+        for (int tb = t0; tb < t1; tb += P) {
 #pragma unroll
-                        for (int v = 0; v < 16; ++v)
-                            if (jbase + tile_row(v, h) >= a.m) acc[v] = ninf;
+            for (int p = 0; p < P; ++p) {
+                const int t = tb + p;
+                if (t < t1) {  // uniform
+                    const Frag cur = ring[p];
+                    ring[p] = O::load(tgt + ((int64_t)min(t + P, t1 - 1) * 32 + c) * O::ROW_BYTES, h);
+                    f32x16 acc[R];
+#pragma unroll
+                    for (int r = 0; r < R; ++r) acc[r] = O::mma(cur, q[r]);
+                    if (t * 32 + 32 > a.m) {  // only the last tile of the map can be partial
+#pragma unroll
+                        for (int r = 0; r < R; ++r)
+#pragma unroll
+                            for (int v = 0; v < 16; ++v)
+                                if (t * 32 + tile_row(v, h) >= a.m) acc[r][v] = ninf;
                     }
-                    // ascending v is ascending candidate index inside the lane; strict ">"
-                    // keeps the lowest index among equal scores
 #pragma unroll
-                    for (int v = 0; v < 16; ++v) {
-                        if (acc[v] > best[r]) {
-                            best[r] = acc[v];
-                            best_j[r] = jbase + tile_row(v, h);
-                        }
+                    for (int r = 0; r < R; ++r) {
+                        const float top = fold16(best[r], acc[r]);
+                        if (top > best[r]) best_tile[r] = t;
+                        best[r] = top;
                     }
                 }
             }
-            cur = nxt;
         }
 
 #pragma unroll
         for (int r = 0; r < R; ++r) {
-            if (r < n_blk) {
-                const float ob = __shfl_xor(best[r], 32);
-                const int oj = __shfl_xor(best_j[r], 32);
-                if (ob > best[r] || (ob == best[r] && oj < best_j[r])) {
-                    best[r] = ob;
-                    best_j[r] = oj;
-                }
-                const int slot = slot0 + r * 32 + c;
-                if (h == 0 && slot < n_act) atomicMax(&a.out_keys[qbase + slot], pack_key(best[r], best_j[r]));
+            const float ob = __shfl_xor(best[r], 32);
+            const int ot = __shfl_xor(best_tile[r], 32);
+            if (ob > best[r] || (ob == best[r] && ot < best_tile[r])) {
+                best[r] = ob;
+                best_tile[r] = ot;
             }
+            const int slot = slot0 + r * 32 + c;
+            if (h == 0 && slot < n_act) atomicMax(&a.out_keys[qbase + slot], pack_key(best[r], best_tile[r]));
         }
     }
 }
 
-__global__ __launch_bounds__(256) void decode_kernel(DecodeArgs a) {
+// Pass 2: one wave per query recomputes the 32 scores of the winning tile with the same
+// matrix instruction (the query replicated into every column, so each score has the bits
+// pass 1 saw) and picks the lowest candidate that attains the maximum.  The key is
+// rewritten with the candidate index; optionally index and score are stored as well.
+template <int CT, int DP>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2)))
+void resolve_kernel(SearchArgs a, int32_t* out_idx, float* out_score) {
+    using O = Ops<CT, DP>;
+    using Frag = typename O::Frag;
+    const int lane = threadIdx.x & 63, c = lane & 31, h = lane >> 5;
+    const int wave = blockIdx.x * 4 + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int n_waves = gridDim.x * 4;
     const int b = blockIdx.y;
     int n_act = a.nq;
     if (a.nq_active) n_act = min(max(a.nq_active[b], 0), a.nq);
-    for (int q = blockIdx.x * blockDim.x + threadIdx.x; q < n_act; q += gridDim.x * blockDim.x) {
-        const u64 k = a.keys[(int64_t)b * a.nq + q];
-        a.out_idx[(int64_t)b * a.nq + q] = key_index(k);
-        if (a.out_score) a.out_score[(int64_t)b * a.nq + q] = key_score(k);
+    const char* src = a.src + (int64_t)b * a.src_bstride;
+    const char* tgt = a.tgt + (int64_t)b * a.tgt_bstride;
+    const int64_t qbase = (int64_t)b * a.nq;
+    const float ninf = -__builtin_inff();
+
+    for (int slot = wave; slot < n_act; slot += n_waves) {
+        const u64 key = a.out_keys[qbase + slot];
+        int32_t idx = -1;
+        float score = ninf;
+        if (key != 0) {
+            const int tile = min(key_index(key), a.m_tiles - 1);
+            const Frag qf = O::load(src + query_row(a, qbase, slot) * O::ROW_BYTES, h);
+            const Frag cand = O::load(tgt + ((int64_t)tile * 32 + c) * O::ROW_BYTES, h);
+            f32x16 acc = O::mma(cand, qf);
+            if (tile * 32 + 32 > a.m) {
+#pragma unroll
+                for (int v = 0; v < 16; ++v)
+                    if (tile * 32 + tile_row(v, h) >= a.m) acc[v] = ninf;
+            }
+            float top = fold16(ninf, acc);
+            top = __builtin_fmaxf(top, __shfl_xor(top, 32));
+            int row = 64;
+#pragma unroll
+            for (int v = 15; v >= 0; --v)
+                if (acc[v] == top) row = tile_row(v, h);
+            row = min(row, __shfl_xor(row, 32));
+            idx = tile * 32 + row;
+            score = top;
+            if (lane == 0) a.out_keys[qbase + slot] = pack_key(score, idx);
+        }
+        if (lane == 0 && out_idx) {
+            out_idx[qbase + slot] = idx;
+            if (out_score) out_score[qbase + slot] = score;
+        }
     }
 }
 
@@ -134,7 +205,7 @@ static hipError_t launch_search_t(const SearchArgs& a, int batch, hipStream_t s)
                               ((a.m_tiles + SEARCH_MIN_TILES - 1) / SEARCH_MIN_TILES);
     const int64_t need = (max_units + SEARCH_WAVES - 1) / SEARCH_WAVES;
     if (need < wgs) wgs = (int)(need > 0 ? need : 1);
-    return launch(TK_SEARCH, search_kernel<CT, DP, SEARCH_R>, dim3(wgs, batch), dim3(SEARCH_WAVES * 64), 0, s, a);
+    return launch(TK_SEARCH, search_kernel<CT, DP, SEARCH_R, SEARCH_P>, dim3(wgs, batch), dim3(SEARCH_WAVES * 64), 0, s, a);
 }
 
 hipError_t launch_search(const SearchArgs& a, int batch, int compute, int dp, hipStream_t s) {
@@ -154,11 +225,30 @@ hipError_t launch_search(const SearchArgs& a, int batch, int compute, int dp, hi
     return hipErrorInvalidValue;
 }
 
-hipError_t launch_decode(const DecodeArgs& a, int batch, hipStream_t s) {
+template <int CT, int DP>
+static hipError_t launch_resolve_t(const SearchArgs& a, int batch, int32_t* out_idx, float* out_score, hipStream_t s) {
+    int wgs = (a.nq + 3) / 4;
+    const int cap = 8192 / batch > 64 ? 8192 / batch : 64;
+    if (wgs > cap) wgs = cap;
+    return launch(TK_RESOLVE, resolve_kernel<CT, DP>, dim3(wgs, batch), dim3(256), 0, s, a, out_idx, out_score);
+}
+
+hipError_t launch_resolve(const SearchArgs& a, int batch, int compute, int dp, int32_t* out_idx, float* out_score,
+                          hipStream_t s) {
     if (a.nq <= 0 || batch <= 0) return hipSuccess;
-    int blocks = (a.nq + 255) / 256;
-    if (blocks > 1024) blocks = 1024;
-    return launch(TK_DECODE, decode_kernel, dim3(blocks, batch), dim3(256), 0, s, a);
+    if (compute == FNN_F16) {
+        if (dp == 16) return launch_resolve_t<CT_F16, 16>(a, batch, out_idx, out_score, s);
+        if (dp == 32) return launch_resolve_t<CT_F16, 32>(a, batch, out_idx, out_score, s);
+    } else if (compute == FNN_BF16) {
+        if (dp == 16) return launch_resolve_t<CT_BF16, 16>(a, batch, out_idx, out_score, s);
+        if (dp == 32) return launch_resolve_t<CT_BF16, 32>(a, batch, out_idx, out_score, s);
+    } else {
+        if (dp == 8) return launch_resolve_t<CT_F32, 8>(a, batch, out_idx, out_score, s);
+        if (dp == 16) return launch_resolve_t<CT_F32, 16>(a, batch, out_idx, out_score, s);
+        if (dp == 24) return launch_resolve_t<CT_F32, 24>(a, batch, out_idx, out_score, s);
+        if (dp == 32) return launch_resolve_t<CT_F32, 32>(a, batch, out_idx, out_score, s);
+    }
+    return hipErrorInvalidValue;
 }
 
 }  // namespace fnn

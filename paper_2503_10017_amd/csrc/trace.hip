@@ -83,12 +83,12 @@ const char* fnn_trace_kind_name(int32_t kind) {
         case TK_PREP: return "prep_kernel";
         case TK_FILL: return "fill_u64_kernel";
         case TK_SEARCH: return "search_kernel";
-        case TK_DECODE: return "decode_kernel";
         case TK_RECIP_INIT: return "recip_init_kernel";
         case TK_RECIP_STEP: return "recip_step_kernel";
         case TK_RECIP_DEDUP: return "recip_dedup_kernel";
         case TK_DENSE: return "dense_kernel";
         case TK_DENSE_FINAL: return "dense_final_kernels";
+        case TK_RESOLVE: return "resolve_kernel";
         default: return "unknown";
     }
 }

@@ -11,13 +11,14 @@ enum TraceKind : int {
     TK_PREP = 0,
     TK_FILL = 1,
     TK_SEARCH = 2,
-    TK_DECODE = 3,
+    TK_UNUSED = 3,
     TK_RECIP_INIT = 4,
     TK_RECIP_STEP = 5,
     TK_RECIP_DEDUP = 6,
     TK_DENSE = 7,
     TK_DENSE_FINAL = 8,
-    TK_COUNT = 9
+    TK_RESOLVE = 9,
+    TK_COUNT = 10
 };
 
 // Returns false when no trace is open or it is full; otherwise hands out the next event pair.
