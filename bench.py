@@ -215,7 +215,7 @@ def main() -> int:
             "roofline": {"kernel": "dense_kernel", "bound": "mfma", "achieved": round(dtf, 2), "peak": PEAK_MFMA_16BIT,
                          "unit": "TFLOP/s", "frac": round(dtf / PEAK_MFMA_16BIT, 4), "traffic": None,
                          "avg_launch_ms": round(dense_ms, 4), "flops_per_launch": dflops,
-                         "note": "algorithmic flops 2*24*N*M; the instruction stream executes 4/3 of that (K padded to 32)"},
+                         "note": "algorithmic flops 2*24*N*M (a K=16 plus a K=8 matrix instruction per 32x32 block, no padding)"},
         }
 
     # ---- CPU oracle on a bounded sample of the same workload (baseline only) ----------------------

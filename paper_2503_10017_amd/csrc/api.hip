@@ -2,6 +2,7 @@
 // fixed kernel sequences.  Nothing here synchronises with the device or allocates memory.
 #include <string.h>
 
+#include "dense_perm.hpp"
 #include "fnn_kernels.hpp"
 
 using namespace fnn;
@@ -21,12 +22,6 @@ struct Carver {
     }
 };
 
-int64_t pow2_at_least(int64_t x) {
-    int64_t p = 1;
-    while (p < x) p <<= 1;
-    return p;
-}
-
 bool valid_dtype(int32_t t) { return t == FNN_F32 || t == FNN_F16 || t == FNN_BF16; }
 
 struct MapsLayout {
@@ -37,10 +32,10 @@ struct MapsLayout {
     int dp;
 };
 
-MapsLayout carve_maps(Carver& cv, int batch, int64_t n, int64_t m, int d, int compute) {
+MapsLayout carve_maps(Carver& cv, int batch, int64_t n, int64_t m, int d, int compute, int64_t n_align = 32) {
     MapsLayout L;
     L.dp = padded_d(d, compute);
-    L.n_pad = round_up(n, 32);
+    L.n_pad = round_up(n, n_align);
     L.m_pad = round_up(m, 32);
     const int es = elem_size(compute);
     L.bstride1 = L.n_pad * L.dp * es;
@@ -76,8 +71,9 @@ RecipLayout carve_recip(Carver& cv, int batch, int64_t n, int64_t m, int d, int6
     L.st.seed_id[0] = (int32_t*)cv.take(per * sizeof(int32_t));
     L.st.seed_id[1] = (int32_t*)cv.take(per * sizeof(int32_t));
     L.st.n_active = (int32_t*)cv.take((size_t)batch * sizeof(int32_t));
-    L.st.sort_len = pow2_at_least(n_seeds > 1 ? n_seeds : 1);
-    L.st.sort_buf = (u64*)cv.take((size_t)batch * L.st.sort_len * sizeof(u64));
+    L.st.n_words = (n + 31) / 32;
+    L.st.bitmap = (uint32_t*)cv.take((size_t)batch * L.st.n_words * sizeof(uint32_t));
+    L.st.word_rank = (int32_t*)cv.take((size_t)batch * L.st.n_words * sizeof(int32_t));
     return L;
 }
 
@@ -90,7 +86,7 @@ struct DenseLayout {
 };
 DenseLayout carve_dense(Carver& cv, int batch, int64_t n, int64_t m, int d, int compute) {
     DenseLayout L;
-    L.maps = carve_maps(cv, batch, n, m, d, compute);
+    L.maps = carve_maps(cv, batch, n, m, d, compute, 32 * DENSE_S);
     // the two key tables are adjacent so that one fill clears both
     L.row_keys = (u64*)cv.take((size_t)batch * (n + m) * sizeof(u64));
     L.col_keys = L.row_keys ? L.row_keys + (size_t)batch * n : nullptr;
@@ -145,10 +141,11 @@ void fill_prep_side(PrepSide& sd, int32_t batch, const fnn_map* maps, int64_t n_
 }
 
 hipError_t prep_both(int32_t batch, const fnn_map* a, const fnn_map* b, const MapsLayout& L, int d, int compute,
-                     hipStream_t s) {
+                     hipStream_t s, bool first_segment_major = false) {
     PrepArgs pa;
     memset(&pa, 0, sizeof(pa));
     fill_prep_side(pa.side[0], batch, a, L.n_pad, L.p1);
+    pa.side[0].segment_major = first_segment_major ? 1 : 0;
     fill_prep_side(pa.side[1], batch, b, L.m_pad, L.p2);
     pa.n_sides = 2;
     pa.batch = batch;
@@ -274,7 +271,9 @@ int32_t fnn_reciprocal(int32_t batch, const fnn_map* d1, const fnn_map* d2, cons
 
     if (ns == 0) {
         // nothing to match: only the counts are defined
-        FNN_TRY(launch_recip_dedup(L.st, 0, batch, seed_i, seed_j, seed_iter, pairs, n_pairs, s));
+        RecipState none = L.st;
+        none.n_words = 0;
+        FNN_TRY(launch_recip_dedup(none, 0, batch, seed_i, seed_j, seed_iter, pairs, n_pairs, s));
         return FNN_OK;
     }
 
@@ -353,7 +352,7 @@ int32_t fnn_mutual_dense(int32_t batch, const fnn_map* d1, const fnn_map* d2, co
     if (st != FNN_OK) return st;
     hipStream_t s = (hipStream_t)stream;
 
-    if (n > 0 && m > 0) FNN_TRY(prep_both(batch, d1, d2, L.maps, d, opts->compute, s));
+    if (n > 0 && m > 0) FNN_TRY(prep_both(batch, d1, d2, L.maps, d, opts->compute, s, true));
     FNN_TRY(launch_fill_u64(L.row_keys, (int64_t)batch * (n + m), 0, s));
 
     DenseArgs da;
@@ -364,31 +363,32 @@ int32_t fnn_mutual_dense(int32_t batch, const fnn_map* d1, const fnn_map* d2, co
     da.d2_bstride = L.maps.bstride2;
     da.n = (int32_t)n;
     da.m = (int32_t)m;
-    da.n_blocks = (int32_t)(L.maps.n_pad / 32);
+    da.n_sb = (int32_t)(L.maps.n_pad / (32 * DENSE_S));
     da.m_tiles = (int32_t)(L.maps.m_pad / 32);
     da.row_keys = L.row_keys;
     da.col_keys = L.col_keys;
-    // workgroup tile: up to 4096 queries (32 KB of LDS keys) x enough candidate groups that
-    // the merges into the global key tables stay rare, while small problems still spread
-    // over the whole chip
-    da.q_per_wg = (int32_t)(L.maps.n_pad < 4096 ? L.maps.n_pad : 4096);
-    if (da.q_per_wg < 32) da.q_per_wg = 32;
-    const int64_t q_wgs = (L.maps.n_pad + da.q_per_wg - 1) / da.q_per_wg;
+    // Workgroup tile: up to 3 query super-blocks (48 KB of LDS keys) x up to 4 candidate
+    // groups.  Larger tiles mean fewer merges into the global key tables; small problems
+    // shrink the tile until the grid covers the chip a few times.
     const int64_t groups_total = (da.m_tiles + DENSE_TILES_PER_GROUP - 1) / DENSE_TILES_PER_GROUP;
-    int64_t groups_per_wg = 16;
-    while (groups_per_wg > 1 && q_wgs * ((groups_total + groups_per_wg - 1) / groups_per_wg) * batch < 2048) groups_per_wg >>= 1;
+    int64_t sb_per_wg = da.n_sb < 3 ? da.n_sb : 3;
+    int64_t groups_per_wg = 4;
+    auto wg_count = [&]() {
+        return ((da.n_sb + sb_per_wg - 1) / sb_per_wg) * ((groups_total + groups_per_wg - 1) / groups_per_wg) * batch;
+    };
+    while (groups_per_wg > 1 && wg_count() < 1024) groups_per_wg >>= 1;
+    while (sb_per_wg > 1 && wg_count() < 1024) --sb_per_wg;
+    da.sb_per_wg = (int32_t)(sb_per_wg > 0 ? sb_per_wg : 1);
     da.groups_per_wg = (int32_t)groups_per_wg;
-    FNN_TRY(launch_dense(da, batch, opts->compute, L.maps.dp, s));
+    if (n > 0 && m > 0) FNN_TRY(launch_dense(da, batch, opts->compute, L.maps.dp, nn12, s12, nn21, s21, s));
+    else if (n > 0) FNN_TRY(launch_fill_i32f32(nn12, s12, (int64_t)batch * n, s));
+    else if (m > 0) FNN_TRY(launch_fill_i32f32(nn21, s21, (int64_t)batch * m, s));
 
     DenseFinalArgs fa;
-    fa.row_keys = L.row_keys;
-    fa.col_keys = L.col_keys;
     fa.n = (int32_t)n;
     fa.m = (int32_t)m;
     fa.nn12 = nn12;
-    fa.s12 = s12;
     fa.nn21 = nn21;
-    fa.s21 = s21;
     fa.pairs = pairs;
     fa.n_pairs = n_pairs;
     fa.block_counts = L.block_counts;

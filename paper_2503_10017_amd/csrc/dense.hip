@@ -3,36 +3,110 @@
 // is still in a register, into BOTH running maxima -- the best candidate j of query i and
 // the best query i of candidate j -- so the quadratic score matrix never exists in memory.
 //
-// A wave keeps J candidate tiles (32 pixels of D2 each) resident together with one running
-// best per resident candidate and result lane, and sweeps the workgroup's query range past
-// them.  Per query block the best candidate over the wave's tiles goes into a per-workgroup
-// key table in LDS; after the sweep the per-candidate bests are reduced across lanes and
-// merged into the global key table; the LDS table is merged into the global one at the end.
-// All merges are 64-bit max operations on (score, inverted index) keys.
+// Pass 1 (dense_kernel) works at about 1.3 vector operations per score by tracking only
+// maxima plus a COARSE location:
+//   * a wave keeps J candidate tiles (32 pixels of D2 each) resident and sweeps query
+//     blocks (32 pixels of D1) past them, two blocks per step;
+//   * best candidate of a query: a 3-input-max fold over the 16 result registers of each
+//     product; the location kept is the wave's group of J tiles (J*32 consecutive candidates);
+//   * best query of a candidate: one 3-input max per result register folds the two query
+//     blocks of a step into a running maximum per (candidate, lane); once per super-block of
+//     S query blocks the 32 lanes are reduced and the winning lane is noted.  D1 is stored
+//     "segment major" (dense_perm.hpp) so that the S queries one lane sees inside a
+//     super-block are S CONSECUTIVE pixels: the location kept is that run of S pixels.
+//   Locations are ordered like the pixels they cover, so "largest score, then lowest
+//   location" (a 64-bit max on packed keys) always keeps the run that holds the lowest
+//   index among equal scores.
+// Pass 2 (dense_resolve_*) recomputes, per query and per candidate, just the winning run
+// with the same matrix instruction -- bit-identical scores -- and names the lowest index
+// that attains the maximum.  Then the reciprocity filter and an ordered compaction.
+#include "dense_perm.hpp"
 #include "fnn_device.hpp"
 #include "fnn_kernels.hpp"
 #include "trace.hpp"
 
 namespace fnn {
 
+__device__ __forceinline__ float max3f(float a, float b, float c) { return __builtin_fmaxf(__builtin_fmaxf(a, b), c); }
 
-template <int CT, int DP, int J>
-__global__ __launch_bounds__(DENSE_WAVES * 64) void dense_kernel(DenseArgs a) {
+__device__ __forceinline__ float fold16f(float seed, const f32x16& x) {
+    const float t0 = max3f(x[0], x[1], x[2]);
+    const float t1 = max3f(x[3], x[4], x[5]);
+    const float t2 = max3f(x[6], x[7], x[8]);
+    const float t3 = max3f(x[9], x[10], x[11]);
+    const float t4 = max3f(x[12], x[13], x[14]);
+    const float t5 = max3f(t0, t1, t2);
+    const float t6 = max3f(t3, t4, x[15]);
+    return max3f(seed, t5, t6);
+}
+
+// One super-block (S query blocks) swept past the wave's J resident candidate tiles.  TAIL
+// selects the variant that masks padding pixels (queries >= n, candidates >= m); it is only
+// needed for the last super-block / last candidate group, so the hot variant carries no
+// masking code at all.
+template <int CT, int DP, bool TAIL>
+__device__ __forceinline__ void dense_sweep(const DenseArgs& a, const typename Ops<CT, DP>::Frag (&cand)[DENSE_J],
+                                            float (&cmax)[DENSE_J][16], const char* qbase, int sbg, int tbase,
+                                            u64* lds_rows, int unit_row, int c, int h) {
     using O = Ops<CT, DP>;
     using Frag = typename O::Frag;
-    extern __shared__ u64 lds_row_keys[];  // [q_per_wg]
+    constexpr int J = DENSE_J, S = DENSE_S;
+    const float ninf = -__builtin_inff();
+    Frag qa = O::load(qbase, h);
+    Frag qb = O::load(qbase + 32 * O::ROW_BYTES, h);
+    for (int t = 0; t < S; t += 2) {
+        // prefetch the next two query blocks (the last step reloads its own)
+        const int tn = min(t + 2, S - 2);
+        const Frag na = O::load(qbase + (int64_t)tn * 32 * O::ROW_BYTES, h);
+        const Frag nb = O::load(qbase + (int64_t)(tn + 1) * 32 * O::ROW_BYTES, h);
+        float ra = ninf, rb = ninf;
+#pragma unroll
+        for (int jt = 0; jt < J; ++jt) {
+            f32x16 xa = O::mma(cand[jt], qa);
+            f32x16 xb = O::mma(cand[jt], qb);
+            if (TAIL) {
+                const int ia = segment_pixel(sbg, t, c);  // pixel of this lane's query in block t
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const bool cand_ok = (tbase + jt) * 32 + tile_row(v, h) < a.m;
+                    if (!cand_ok || ia >= a.n) xa[v] = ninf;
+                    if (!cand_ok || ia + 1 >= a.n) xb[v] = ninf;
+                }
+            }
+            ra = fold16f(ra, xa);
+            rb = fold16f(rb, xb);
+#pragma unroll
+            for (int v = 0; v < 16; ++v) cmax[jt][v] = max3f(cmax[jt][v], xa[v], xb[v]);
+        }
+        // best candidate of the two queries over this wave's J tiles -> workgroup table
+        ra = __builtin_fmaxf(ra, __shfl_xor(ra, 32));
+        rb = __builtin_fmaxf(rb, __shfl_xor(rb, 32));
+        const float mine = h ? rb : ra;  // half 0 files block t, half 1 block t+1
+        if (!TAIL || mine != ninf) atomicMax(&lds_rows[(t + h) * 32 + c], pack_key(mine, unit_row));
+        qa = na;
+        qb = nb;
+    }
+}
 
+template <int CT, int DP>
+__global__ __launch_bounds__(DENSE_WAVES * 64) __attribute__((amdgpu_waves_per_eu(2)))
+void dense_kernel(DenseArgs a) {
+    using O = Ops<CT, DP>;
+    using Frag = typename O::Frag;
+    constexpr int J = DENSE_J, S = DENSE_S;
+    extern __shared__ u64 lds[];
+    u64* lds_row_keys = lds;  // [sb_per_wg * S * 32], indexed by the query's stored slot in the workgroup's range
     const int lane = threadIdx.x & 63, c = lane & 31, h = lane >> 5;
-    const int wave = threadIdx.x >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    u64* lds_col_keys = lds + (size_t)a.sb_per_wg * S * 32 + wave * (J * 32);  // this wave's J*32 candidates
     const int b = blockIdx.z;
     const float ninf = -__builtin_inff();
 
-    const int q0 = blockIdx.y * a.q_per_wg;                       // first query of this workgroup
-    const int q_blocks = min(a.q_per_wg / 32, a.n_blocks - q0 / 32);
-    const int tiles_per_group = DENSE_WAVES * J;
-    const int tile0 = blockIdx.x * a.groups_per_wg * tiles_per_group;
+    const int sb0 = blockIdx.y * a.sb_per_wg;          // first super-block of this workgroup
+    const int n_sb = min(a.sb_per_wg, a.n_sb - sb0);
+    const int group0 = blockIdx.x * a.groups_per_wg;   // first candidate group (DENSE_WAVES*J tiles)
 
-    for (int i = threadIdx.x; i < a.q_per_wg; i += blockDim.x) lds_row_keys[i] = 0;
+    for (int i = threadIdx.x; i < a.sb_per_wg * S * 32; i += blockDim.x) lds_row_keys[i] = 0;
     __syncthreads();
 
     const char* d1 = a.d1 + (int64_t)b * a.d1_bstride;
@@ -41,118 +115,184 @@ __global__ __launch_bounds__(DENSE_WAVES * 64) void dense_kernel(DenseArgs a) {
     u64* col_keys = a.col_keys + (int64_t)b * a.m;
 
     for (int g = 0; g < a.groups_per_wg; ++g) {
-        const int tbase = tile0 + g * tiles_per_group + wave * J;
-        if (tbase >= a.m_tiles) break;  // uniform per wave; no barrier inside this loop
+        const int tbase = ((group0 + g) * DENSE_WAVES + wave) * J;  // this wave's first candidate tile
+        if (tbase >= a.m_tiles) break;                              // uniform per wave; no barrier in this loop
 
         Frag cand[J];
-        float cbest[J][16];
-        int cblk[J][16];
 #pragma unroll
         for (int jt = 0; jt < J; ++jt) {
-            const int t = min(tbase + jt, a.m_tiles - 1);
-            cand[jt] = O::load(d2 + ((int64_t)t * 32 + c) * O::ROW_BYTES, h);
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                cbest[jt][v] = ninf;
-                cblk[jt][v] = 0;
-            }
+            cand[jt] = O::load(d2 + ((int64_t)min(tbase + jt, a.m_tiles - 1) * 32 + c) * O::ROW_BYTES, h);
+            lds_col_keys[jt * 32 + c] = 0;  // both lane halves store the same zero
         }
+        const bool cand_tail = (tbase + J) * 32 > a.m;              // some resident candidate is past the map
 
-        for (int ib = 0; ib < q_blocks; ++ib) {
-            const int i = q0 + ib * 32 + c;  // this lane's query
-            const Frag q = O::load(d1 + (int64_t)i * O::ROW_BYTES, h);
-            const bool q_valid = i < a.n;
-            float rbest = ninf;
-            int rj = 0x7FFFFFFF;
+        for (int sb = 0; sb < n_sb; ++sb) {
+            const int sbg = sb0 + sb;
+            const bool query_tail = (sbg + 1) * (32 * S) > a.n;     // some query of this super-block is padding
+            float cmax[J][16];
+#pragma unroll
+            for (int jt = 0; jt < J; ++jt)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) cmax[jt][v] = ninf;
+
+            const char* qbase = d1 + ((int64_t)sbg * S * 32 + c) * O::ROW_BYTES;
+            if (cand_tail || query_tail)
+                dense_sweep<CT, DP, true>(a, cand, cmax, qbase, sbg, tbase, lds_row_keys + sb * S * 32, tbase / J, c, h);
+            else
+                dense_sweep<CT, DP, false>(a, cand, cmax, qbase, sbg, tbase, lds_row_keys + sb * S * 32, tbase / J, c, h);
+
+            // best query of each resident candidate inside this super-block: reduce the 32
+            // lanes of each half and note the lowest lane that attains the maximum
 #pragma unroll
             for (int jt = 0; jt < J; ++jt) {
-                const int t = tbase + jt;
-                if (t < a.m_tiles) {
-                    f32x16 acc = O::mma(cand[jt], q);
-                    const int jbase = t * 32;
-                    if (!q_valid) {
-#pragma unroll
-                        for (int v = 0; v < 16; ++v) acc[v] = ninf;
-                    }
-                    if (jbase + 32 > a.m) {
-#pragma unroll
-                        for (int v = 0; v < 16; ++v)
-                            if (jbase + tile_row(v, h) >= a.m) acc[v] = ninf;
-                    }
-#pragma unroll
-                    for (int v = 0; v < 16; ++v) {
-                        // best candidate of this query: ascending v, ascending jt = ascending j
-                        if (acc[v] > rbest) {
-                            rbest = acc[v];
-                            rj = jbase + tile_row(v, h);
-                        }
-                        // best query of this candidate: ascending ib = ascending i in this lane
-                        if (acc[v] > cbest[jt][v]) {
-                            cbest[jt][v] = acc[v];
-                            cblk[jt][v] = ib;
-                        }
-                    }
-                }
-            }
-            const float ob = __shfl_xor(rbest, 32);
-            const int oj = __shfl_xor(rj, 32);
-            if (ob > rbest || (ob == rbest && oj < rj)) {
-                rbest = ob;
-                rj = oj;
-            }
-            if (h == 0 && q_valid && rj != 0x7FFFFFFF)
-                atomicMax(&lds_row_keys[ib * 32 + c], pack_key(rbest, rj));
-        }
-
-        // per-candidate bests: reduce over the 32 lanes (queries) of each half, then merge
-#pragma unroll
-        for (int jt = 0; jt < J; ++jt) {
-            const int t = tbase + jt;
-            if (t < a.m_tiles) {
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
-                    u64 key = 0;
-                    if (cbest[jt][v] != ninf) key = pack_key(cbest[jt][v], q0 + cblk[jt][v] * 32 + c);
+                    const float x = cmax[jt][v];
+                    float top = x;
 #pragma unroll
-                    for (int mask = 1; mask < 32; mask <<= 1) {
-                        const u64 other = shfl_xor_u64(key, mask);
-                        key = other > key ? other : key;
-                    }
-                    const int j = t * 32 + tile_row(v, h);
-                    if (c == 0 && j < a.m && key) atomicMax(&col_keys[j], key);
+                    for (int mask = 1; mask < 32; mask <<= 1) top = __builtin_fmaxf(top, __shfl_xor(top, mask));
+                    const u64 hit = __ballot(x == top);
+                    const int lane_lo = __ffsll((unsigned long long)(hit & 0xFFFFFFFFull)) - 1;
+                    const int lane_hi = __ffsll((unsigned long long)(hit >> 32)) - 1;
+                    const int winner = h ? lane_hi : lane_lo;
+                    if (c == 0 && top != ninf)
+                        atomicMax(&lds_col_keys[jt * 32 + tile_row(v, h)], pack_key(top, sbg * 32 + winner));
                 }
             }
+        }
+
+        // this wave's candidates are complete for the workgroup's query range
+#pragma unroll
+        for (int jt = 0; jt < J; ++jt) {
+            const int j = (tbase + jt) * 32 + c;
+            const u64 key = lds_col_keys[jt * 32 + c];
+            if (h == 0 && j < a.m && key) atomicMax(&col_keys[j], key);
         }
     }
 
     __syncthreads();
-    for (int i = threadIdx.x; i < a.q_per_wg; i += blockDim.x) {
-        const u64 key = lds_row_keys[i];
-        if (key && q0 + i < a.n) atomicMax(&row_keys[q0 + i], key);
+    for (int slot = threadIdx.x; slot < n_sb * S * 32; slot += blockDim.x) {
+        const u64 key = lds_row_keys[slot];
+        const int i = segment_pixel(sb0 + slot / (S * 32), (slot / 32) % S, slot % 32);
+        if (key && i < a.n) atomicMax(&row_keys[i], key);
     }
 }
 
-// ---- decode the key tables, apply the reciprocity filter, compact the pairs in order ----
+// Pass 2, queries: one wave per pixel i of image 1 recomputes the J tiles of the winning
+// group with i replicated into every column and picks the lowest candidate at the maximum.
+template <int CT, int DP>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2)))
+void dense_resolve_rows_kernel(DenseArgs a, int32_t* nn12, float* s12) {
+    using O = Ops<CT, DP>;
+    using Frag = typename O::Frag;
+    constexpr int J = DENSE_J;
+    const int lane = threadIdx.x & 63, c = lane & 31, h = lane >> 5;
+    const int wave = blockIdx.x * 4 + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int n_waves = gridDim.x * 4;
+    const int b = blockIdx.y;
+    const char* d1 = a.d1 + (int64_t)b * a.d1_bstride;
+    const char* d2 = a.d2 + (int64_t)b * a.d2_bstride;
+    const float ninf = -__builtin_inff();
+    for (int i = wave; i < a.n; i += n_waves) {
+        const u64 key = a.row_keys[(int64_t)b * a.n + i];
+        int32_t best_j = -1;
+        float best = ninf;
+        if (key != 0) {
+            const int tbase = min(key_index(key), (a.m_tiles - 1) / J) * J;
+            const Frag q = O::load(d1 + segment_slot(i) * O::ROW_BYTES, h);
+            Frag cand[J];
+#pragma unroll
+            for (int jt = 0; jt < J; ++jt)
+                cand[jt] = O::load(d2 + ((int64_t)min(tbase + jt, a.m_tiles - 1) * 32 + c) * O::ROW_BYTES, h);
+#pragma unroll
+            for (int jt = J - 1; jt >= 0; --jt) {  // descending, so that ">=" ends on the lowest tile
+                if (tbase + jt < a.m_tiles) {
+                    f32x16 x = O::mma(cand[jt], q);
+#pragma unroll
+                    for (int v = 0; v < 16; ++v)
+                        if ((tbase + jt) * 32 + tile_row(v, h) >= a.m) x[v] = ninf;
+                    float top = fold16f(ninf, x);
+                    top = __builtin_fmaxf(top, __shfl_xor(top, 32));
+                    int row = 64;
+#pragma unroll
+                    for (int v = 15; v >= 0; --v)
+                        if (x[v] == top) row = tile_row(v, h);
+                    row = min(row, __shfl_xor(row, 32));
+                    if (top >= best) {
+                        best = top;
+                        best_j = (tbase + jt) * 32 + row;
+                    }
+                }
+            }
+        }
+        if (lane == 0) {
+            nn12[(int64_t)b * a.n + i] = best_j;
+            if (s12) s12[(int64_t)b * a.n + i] = best;
+        }
+    }
+}
+
+// Pass 2, candidates: one wave per pixel j of image 2 recomputes its scores against the S
+// consecutive queries of the winning run (j replicated into every row) and picks the lowest
+// query at the maximum.
+template <int CT, int DP>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2)))
+void dense_resolve_cols_kernel(DenseArgs a, int32_t* nn21, float* s21) {
+    using O = Ops<CT, DP>;
+    using Frag = typename O::Frag;
+    constexpr int S = DENSE_S;
+    const int lane = threadIdx.x & 63, c = lane & 31, h = lane >> 5;
+    const int wave = blockIdx.x * 4 + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int n_waves = gridDim.x * 4;
+    const int b = blockIdx.y;
+    const char* d1 = a.d1 + (int64_t)b * a.d1_bstride;
+    const char* d2 = a.d2 + (int64_t)b * a.d2_bstride;
+    const float ninf = -__builtin_inff();
+    for (int j = wave; j < a.m; j += n_waves) {
+        const u64 key = a.col_keys[(int64_t)b * a.m + j];
+        int32_t best_i = -1;
+        float best = ninf;
+        if (key != 0) {
+            const int64_t run0 = (int64_t)min(key_index(key), a.n_sb * 32 - 1) * S;  // first pixel of the run
+            const Frag cand = O::load(d2 + (int64_t)j * O::ROW_BYTES, h);
+            Frag q[S / 32];
+#pragma unroll
+            for (int part = 0; part < S / 32; ++part)
+                q[part] = O::load(d1 + segment_slot(run0 + part * 32 + c) * O::ROW_BYTES, h);
+#pragma unroll
+            for (int part = S / 32 - 1; part >= 0; --part) {  // descending, ">=" ends on the lowest part
+                const f32x16 x = O::mma(cand, q[part]);
+                const int64_t i = run0 + part * 32 + c;
+                const float mine = i < a.n ? x[0] : ninf;      // every row of the product is candidate j
+                float top = mine;
+#pragma unroll
+                for (int mask = 1; mask < 32; mask <<= 1) top = __builtin_fmaxf(top, __shfl_xor(top, mask));
+                const u64 hit = __ballot(mine == top) & 0xFFFFFFFFull;
+                top = __shfl(top, 0);
+                if (hit && top >= best) {
+                    best = top;
+                    best_i = (int32_t)(run0 + part * 32 + (__ffsll((unsigned long long)hit) - 1));
+                }
+            }
+        }
+        if (lane == 0) {
+            nn21[(int64_t)b * a.m + j] = best_i;
+            if (s21) s21[(int64_t)b * a.m + j] = best;
+        }
+    }
+}
+
+// ---- reciprocity filter and ordered compaction of the pairs ------------------------------
 constexpr int FINAL_THREADS = 1024;
 
-__global__ __launch_bounds__(FINAL_THREADS) void dense_decode_kernel(DenseFinalArgs a, int blocks_per_pair) {
+__global__ __launch_bounds__(FINAL_THREADS) void dense_count_kernel(DenseFinalArgs a, int blocks_per_pair) {
     __shared__ int wave_sums[17];
     const int b = blockIdx.y;
     const int i = blockIdx.x * FINAL_THREADS + threadIdx.x;
-    const u64* row_keys = a.row_keys + (int64_t)b * a.n;
-    const u64* col_keys = a.col_keys + (int64_t)b * a.m;
     bool mutual = false;
     if (i < a.n) {
-        const u64 k = row_keys[i];
-        const int32_t j = key_index(k);
-        a.nn12[(int64_t)b * a.n + i] = j;
-        if (a.s12) a.s12[(int64_t)b * a.n + i] = key_score(k);
-        if (j >= 0 && j < a.m) mutual = key_index(col_keys[j]) == i;
-    }
-    if (i < a.m) {
-        const u64 k = col_keys[i];
-        a.nn21[(int64_t)b * a.m + i] = key_index(k);
-        if (a.s21) a.s21[(int64_t)b * a.m + i] = key_score(k);
+        const int32_t j = a.nn12[(int64_t)b * a.n + i];
+        if (j >= 0 && j < a.m) mutual = a.nn21[(int64_t)b * a.m + j] == i;
     }
     int total;
     block_scan_flag(mutual, wave_sums, total);
@@ -168,7 +308,6 @@ __global__ __launch_bounds__(FINAL_THREADS) void dense_scan_kernel(DenseFinalArg
     for (int start = 0; start < blocks_per_pair; start += FINAL_THREADS) {
         const int i = start + (int)threadIdx.x;
         const int v = i < blocks_per_pair ? counts[i] : 0;
-        // inclusive scan inside the wave, then across waves
         int x = v;
         const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
 #pragma unroll
@@ -217,26 +356,39 @@ __global__ __launch_bounds__(FINAL_THREADS) void dense_scatter_kernel(DenseFinal
 }
 
 template <int CT, int DP>
-static hipError_t launch_dense_t(const DenseArgs& a, int batch, hipStream_t s) {
-    const int tiles_per_wg = a.groups_per_wg * DENSE_WAVES * DENSE_J;
-    dim3 grid((a.m_tiles + tiles_per_wg - 1) / tiles_per_wg, (a.n_blocks * 32 + a.q_per_wg - 1) / a.q_per_wg, batch);
-    return launch(TK_DENSE, dense_kernel<CT, DP, DENSE_J>, grid, dim3(DENSE_WAVES * 64),
-                  (size_t)a.q_per_wg * sizeof(u64), s, a);
+static hipError_t launch_dense_t(const DenseArgs& a, int batch, int32_t* nn12, float* s12, int32_t* nn21, float* s21,
+                                 hipStream_t s) {
+    const int groups = (a.m_tiles + DENSE_TILES_PER_GROUP - 1) / DENSE_TILES_PER_GROUP;
+    dim3 grid((groups + a.groups_per_wg - 1) / a.groups_per_wg, (a.n_sb + a.sb_per_wg - 1) / a.sb_per_wg, batch);
+    const size_t lds_bytes = ((size_t)a.sb_per_wg * DENSE_S * 32 + DENSE_WAVES * DENSE_J * 32) * sizeof(u64);
+    hipError_t e = launch(TK_DENSE, dense_kernel<CT, DP>, grid, dim3(DENSE_WAVES * 64), lds_bytes, s, a);
+    if (e != hipSuccess) return e;
+    const int cap = 8192 / batch > 64 ? 8192 / batch : 64;
+    int wgs = (a.n + 3) / 4;
+    if (wgs > cap) wgs = cap;
+    e = launch(TK_DENSE_RESOLVE, dense_resolve_rows_kernel<CT, DP>, dim3(wgs, batch), dim3(256), 0, s, a, nn12, s12);
+    if (e != hipSuccess) return e;
+    wgs = (a.m + 3) / 4;
+    if (wgs > cap) wgs = cap;
+    return launch(TK_DENSE_RESOLVE, dense_resolve_cols_kernel<CT, DP>, dim3(wgs, batch), dim3(256), 0, s, a, nn21, s21);
 }
 
-hipError_t launch_dense(const DenseArgs& a, int batch, int compute, int dp, hipStream_t s) {
+hipError_t launch_dense(const DenseArgs& a, int batch, int compute, int dp, int32_t* nn12, float* s12, int32_t* nn21,
+                        float* s21, hipStream_t s) {
     if (a.n <= 0 || a.m <= 0 || batch <= 0) return hipSuccess;
     if (compute == FNN_F16) {
-        if (dp == 16) return launch_dense_t<CT_F16, 16>(a, batch, s);
-        if (dp == 32) return launch_dense_t<CT_F16, 32>(a, batch, s);
+        if (dp == 16) return launch_dense_t<CT_F16, 16>(a, batch, nn12, s12, nn21, s21, s);
+        if (dp == 24) return launch_dense_t<CT_F16, 24>(a, batch, nn12, s12, nn21, s21, s);
+        if (dp == 32) return launch_dense_t<CT_F16, 32>(a, batch, nn12, s12, nn21, s21, s);
     } else if (compute == FNN_BF16) {
-        if (dp == 16) return launch_dense_t<CT_BF16, 16>(a, batch, s);
-        if (dp == 32) return launch_dense_t<CT_BF16, 32>(a, batch, s);
+        if (dp == 16) return launch_dense_t<CT_BF16, 16>(a, batch, nn12, s12, nn21, s21, s);
+        if (dp == 24) return launch_dense_t<CT_BF16, 24>(a, batch, nn12, s12, nn21, s21, s);
+        if (dp == 32) return launch_dense_t<CT_BF16, 32>(a, batch, nn12, s12, nn21, s21, s);
     } else {
-        if (dp == 8) return launch_dense_t<CT_F32, 8>(a, batch, s);
-        if (dp == 16) return launch_dense_t<CT_F32, 16>(a, batch, s);
-        if (dp == 24) return launch_dense_t<CT_F32, 24>(a, batch, s);
-        if (dp == 32) return launch_dense_t<CT_F32, 32>(a, batch, s);
+        if (dp == 8) return launch_dense_t<CT_F32, 8>(a, batch, nn12, s12, nn21, s21, s);
+        if (dp == 16) return launch_dense_t<CT_F32, 16>(a, batch, nn12, s12, nn21, s21, s);
+        if (dp == 24) return launch_dense_t<CT_F32, 24>(a, batch, nn12, s12, nn21, s21, s);
+        if (dp == 32) return launch_dense_t<CT_F32, 32>(a, batch, nn12, s12, nn21, s21, s);
     }
     return hipErrorInvalidValue;
 }
@@ -245,7 +397,7 @@ hipError_t launch_dense_final(const DenseFinalArgs& a, int batch, hipStream_t s)
     const int most = a.n > a.m ? a.n : a.m;
     const int blocks = (most + FINAL_THREADS - 1) / FINAL_THREADS;
     if (blocks == 0 || batch <= 0) return hipSuccess;
-    hipError_t e = launch(TK_DENSE_FINAL, dense_decode_kernel, dim3(blocks, batch), dim3(FINAL_THREADS), 0, s, a, blocks);
+    hipError_t e = launch(TK_DENSE_FINAL, dense_count_kernel, dim3(blocks, batch), dim3(FINAL_THREADS), 0, s, a, blocks);
     if (e != hipSuccess) return e;
     e = launch(TK_DENSE_FINAL, dense_scan_kernel, dim3(batch), dim3(FINAL_THREADS), 0, s, a, blocks);
     if (e != hipSuccess) return e;

@@ -7,6 +7,8 @@ namespace fnn {
 
 typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
+typedef short i16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef unsigned long long u64;
 
@@ -46,9 +48,10 @@ __device__ __forceinline__ u64 shfl_xor_u64(u64 v, int mask) {
 
 // ---------------------------------------------------------------------------------------
 // Matrix-core fragments.  A prepared map stores DP elements per pixel (zero padded).  In a
-// 32-pixel tile lane (c = lane & 31, h = lane >> 5) owns pixel c and the contiguous half
-// [h*DP/2, (h+1)*DP/2) of its channels, for the operand on either side of the product, so
-// both sides agree on which channel sits in which slot of which matrix instruction.
+// 32-pixel tile lane (c = lane & 31, h = lane >> 5) owns pixel c and a fixed half of its
+// channels (the contiguous half [h*DP/2, (h+1)*DP/2) in the generic layout), for the
+// operand on either side of the product, so both sides agree on which channel sits in
+// which slot of which matrix instruction.
 // mma(a, b): a = 32 candidate pixels, b = 32 query pixels.  Result register v of lane (c, h)
 // is the score of query c against candidate 8*(v/4) + 4*h + (v%4) of the tile.
 // ---------------------------------------------------------------------------------------
@@ -92,6 +95,47 @@ struct Ops {
         return acc;
     }
 };
+
+// 24 channels in a 16-bit format: 48-byte rows, no padding.  Channels 0..15 go through one
+// K=16 matrix instruction (lane half h supplies channels 8h..8h+7), channels 16..23 through
+// one K=8 instruction (lane half h supplies channels 16+4h..16+4h+3).
+template <int CT>
+struct OpsHalf24 {
+    static constexpr int ESIZE = 2;
+    static constexpr int ROW_BYTES = 48;
+
+    struct Frag {
+        uint4 lo;
+        uint2 hi;
+    };
+
+    static __device__ __forceinline__ Frag load(const char* row, int h) {
+        Frag f;
+        f.lo = *reinterpret_cast<const uint4*>(row + 16 * h);
+        f.hi = *reinterpret_cast<const uint2*>(row + 32 + 8 * h);
+        return f;
+    }
+
+    static __device__ __forceinline__ f32x16 mma(const Frag& a, const Frag& b) {
+        f32x16 acc = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        if constexpr (CT == CT_F16) {
+            acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a.lo), __builtin_bit_cast(f16x8, b.lo),
+                                                         acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_32x32x8f16(__builtin_bit_cast(f16x4, a.hi), __builtin_bit_cast(f16x4, b.hi),
+                                                       acc, 0, 0, 0);
+        } else {
+            acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a.lo),
+                                                          __builtin_bit_cast(bf16x8, b.lo), acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_32x32x8bf16_1k(__builtin_bit_cast(i16x4, a.hi),
+                                                           __builtin_bit_cast(i16x4, b.hi), acc, 0, 0, 0);
+        }
+        return acc;
+    }
+};
+template <>
+struct Ops<CT_F16, 24> : OpsHalf24<CT_F16> {};
+template <>
+struct Ops<CT_BF16, 24> : OpsHalf24<CT_BF16> {};
 
 // Candidate offset inside a tile of result register v for lane half h.
 __device__ __forceinline__ constexpr int tile_row(int v, int h) { return 8 * (v >> 2) + 4 * h + (v & 3); }

@@ -10,11 +10,12 @@ namespace fnn {
 
 typedef unsigned long long u64;
 
-// Padded channel count of a prepared map: 16-bit formats use one or two K=16 matrix
-// instructions, fp32 uses K=2 instructions on channel pairs.
+// Padded channel count of a prepared map: 16-bit formats use one K=16 matrix instruction,
+// a K=16 and a K=8 one (24 channels, no padding for the paper's d = 24) or two K=16 ones;
+// fp32 uses K=2 instructions on channel pairs.
 inline int padded_d(int d, int compute) {
     if (compute == FNN_F32) return (d + 7) / 8 * 8;
-    return d <= 16 ? 16 : 32;
+    return d <= 16 ? 16 : (d <= 24 ? 24 : 32);
 }
 inline int elem_size(int dtype) { return dtype == FNN_F32 ? 4 : 2; }
 inline int64_t round_up(int64_t x, int64_t a) { return (x + a - 1) / a * a; }
@@ -24,6 +25,7 @@ struct PrepSide {
     const void* src[FNN_MAX_BATCH];  // device pointers, one per pair
     int64_t n;                       // valid pixels
     int64_t n_pad;                   // rows written per pair (multiple of 32; rows >= n are zero)
+    int32_t segment_major;           // 1: rows are stored in the dense kernel's segment-major order
     int64_t row_stride;              // source row stride, elements
     int32_t dtype;                   // source storage format
     void* dst;                       // [batch][n_pad][dp] in the compute format
@@ -38,6 +40,8 @@ struct PrepArgs {
 };
 hipError_t launch_prep(const PrepArgs& a, hipStream_t s);
 hipError_t launch_fill_u64(u64* p, int64_t count, u64 value, hipStream_t s);
+// "no neighbour": idx = -1, score = -inf (score may be NULL)
+hipError_t launch_fill_i32f32(int32_t* idx, float* score, int64_t count, hipStream_t s);
 
 // ---- one-directional search ------------------------------------------------------------
 struct SearchArgs {
@@ -68,8 +72,9 @@ struct RecipState {
     int32_t* n_active;   // [batch]
     u64* keys_f;         // [batch][n_seeds] result of the search into image 2 (V^t)
     u64* keys_b;         // [batch][n_seeds] result of the search back into image 1 (U^{t+1})
-    u64* sort_buf;       // [batch][sort_len] scratch for the final sort when it exceeds LDS
-    int64_t sort_len;
+    uint32_t* bitmap;    // [batch][n_words] one bit per pixel of image 1, for the final sort
+    int32_t* word_rank;  // [batch][n_words] rank of the first bit of each bitmap word
+    int64_t n_words;
 };
 hipError_t launch_recip_init(const RecipState& st, const int32_t* seeds, int32_t n_seeds, int batch, hipStream_t s);
 // mode 0: ordinary iteration t; 1: last iteration (survivors are reported as unconverged);
@@ -81,31 +86,31 @@ hipError_t launch_recip_dedup(const RecipState& st, int32_t n_seeds, int batch,
                               int32_t* pairs, int32_t* n_pairs, hipStream_t s);
 
 // ---- dense mutual nearest neighbours -----------------------------------------------------
+constexpr int DENSE_J = 4;      // candidate tiles resident per wave
+constexpr int DENSE_WAVES = 8;  // waves per workgroup
+constexpr int DENSE_TILES_PER_GROUP = DENSE_J * DENSE_WAVES;
 struct DenseArgs {
-    const char* d1;        // prepared queries [batch][n_pad][dp]
+    const char* d1;        // prepared queries, segment-major, [batch][n_sb*32*DENSE_S][dp]
     int64_t d1_bstride;
-    const char* d2;        // prepared candidates [batch][m_pad][dp]
+    const char* d2;        // prepared candidates, natural order, [batch][m_tiles*32][dp]
     int64_t d2_bstride;
     int32_t n, m;
-    int32_t n_blocks, m_tiles;  // 32-pixel blocks per side
-    u64* row_keys;         // [batch][n] zero-initialised
-    u64* col_keys;         // [batch][m] zero-initialised
-    int32_t q_per_wg;      // queries per workgroup (multiple of 32)
-    int32_t groups_per_wg; // candidate groups (of 4 waves x J tiles) per workgroup
+    int32_t n_sb;          // super-blocks of queries (32*DENSE_S pixels each)
+    int32_t m_tiles;       // 32-pixel tiles of candidates
+    u64* row_keys;         // [batch][n] zero-initialised; (best score, group of DENSE_J tiles)
+    u64* col_keys;         // [batch][m] zero-initialised; (best score, run of DENSE_S queries)
+    int32_t sb_per_wg;     // super-blocks swept by one workgroup
+    int32_t groups_per_wg; // candidate groups (DENSE_WAVES x DENSE_J tiles) per workgroup
 };
-constexpr int DENSE_J = 2;      // candidate tiles resident per wave
-constexpr int DENSE_WAVES = 4;  // waves per workgroup
-constexpr int DENSE_TILES_PER_GROUP = DENSE_J * DENSE_WAVES;
-hipError_t launch_dense(const DenseArgs& a, int batch, int compute, int dp, hipStream_t s);
+// Pass 1 (both maxima with coarse locations) and pass 2 (exact indices and scores into
+// nn12/s12/nn21/s21; s12, s21 may be NULL).
+hipError_t launch_dense(const DenseArgs& a, int batch, int compute, int dp, int32_t* nn12, float* s12, int32_t* nn21,
+                        float* s21, hipStream_t s);
 
 struct DenseFinalArgs {
-    const u64* row_keys;
-    const u64* col_keys;
     int32_t n, m;
-    int32_t* nn12;
-    float* s12;   // may be NULL
-    int32_t* nn21;
-    float* s21;   // may be NULL
+    const int32_t* nn12;
+    const int32_t* nn21;
     int32_t* pairs;       // [batch][min(n,m)][2]
     int32_t* n_pairs;     // [batch]
     int32_t* block_counts;  // [batch][ceil(max(n,m)/1024)] scratch

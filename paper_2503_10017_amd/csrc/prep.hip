@@ -2,6 +2,7 @@
 // matrix instructions consume -- the compute format of Algorithm 3 ("HybridCast": inputs
 // rounded to 16 bits, round-to-nearest-even) or plain fp32 -- with the channel count zero
 // padded to the instruction's K and the pixel count zero padded to whole 32-pixel tiles.
+#include "dense_perm.hpp"
 #include "fnn_device.hpp"
 #include "fnn_kernels.hpp"
 #include "trace.hpp"
@@ -40,13 +41,14 @@ __global__ __launch_bounds__(256) void prep_kernel(PrepArgs a) {
     const void* src = sd.src[b];
     for (int64_t item = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; item < total;
          item += (int64_t)gridDim.x * blockDim.x) {
-        const int64_t row = item / groups;
+        const int64_t row = item / groups;                               // stored row
+        const int64_t pix = sd.segment_major ? slot_pixel(row) : row;   // pixel it holds
         const int g = (int)(item % groups);
         float v[8];
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
             const int k = g * 8 + e;
-            v[e] = (row < sd.n && k < a.d) ? load_as_float(src, row * sd.row_stride + k, sd.dtype) : 0.0f;
+            v[e] = (pix < sd.n && k < a.d) ? load_as_float(src, pix * sd.row_stride + k, sd.dtype) : 0.0f;
         }
         if (a.compute == FNN_F32) {
             float4* out = reinterpret_cast<float4*>(dst + (row * a.dp + g * 8) * 4);
@@ -70,6 +72,20 @@ __global__ __launch_bounds__(256) void prep_kernel(PrepArgs a) {
 __global__ __launch_bounds__(256) void fill_u64_kernel(u64* p, int64_t count, u64 value) {
     for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < count; i += (int64_t)gridDim.x * blockDim.x)
         p[i] = value;
+}
+
+__global__ __launch_bounds__(256) void fill_none_kernel(int32_t* idx, float* score, int64_t count) {
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < count; i += (int64_t)gridDim.x * blockDim.x) {
+        idx[i] = -1;
+        if (score) score[i] = -__builtin_inff();
+    }
+}
+
+hipError_t launch_fill_i32f32(int32_t* idx, float* score, int64_t count, hipStream_t s) {
+    if (count <= 0) return hipSuccess;
+    int64_t blocks = (count + 255) / 256;
+    if (blocks > 2048) blocks = 2048;
+    return launch(TK_FILL, fill_none_kernel, dim3((unsigned)blocks), dim3(256), 0, s, idx, score, count);
 }
 
 hipError_t launch_prep(const PrepArgs& a, hipStream_t s) {

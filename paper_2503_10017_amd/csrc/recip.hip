@@ -1,7 +1,7 @@
 // Bookkeeping of the FastNN iteration (paper section 3.2, "FastNN Algorithm", steps 1-4):
 // the reciprocity test U^{t+1} == U^t, the removal of converged seeds by a prefix-sum
 // compaction of the ones still moving, and the final reduction of the matches to a sorted
-// set.  Everything lives on the device: the host enqueues a fixed sequence of kernels and
+// set (a distribution sort over the pixel range).  Everything lives on the device: the host enqueues a fixed sequence of kernels and
 // never reads a count back.
 #include "fnn_device.hpp"
 #include "fnn_kernels.hpp"
@@ -14,6 +14,8 @@ constexpr int STEP_THREADS = 1024;
 __global__ __launch_bounds__(256) void recip_init_kernel(RecipState st, const int32_t* seeds, int32_t n_seeds) {
     const int b = blockIdx.y;
     const int64_t base = (int64_t)b * n_seeds;
+    for (int64_t w = blockIdx.x * blockDim.x + threadIdx.x; w < st.n_words; w += gridDim.x * blockDim.x)
+        st.bitmap[(int64_t)b * st.n_words + w] = 0;
     for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < n_seeds; i += gridDim.x * blockDim.x) {
         st.cur_u[0][base + i] = seeds[base + i];
         st.seed_id[0][base + i] = i;
@@ -90,61 +92,81 @@ struct DedupArgs {
     const int32_t* seed_j;
     const int32_t* seed_iter;
     int32_t n_seeds;
-    int32_t n_sort;     // power of two >= n_seeds
-    u64* global_buf;    // [batch][n_sort] when the keys do not fit in LDS, else NULL
+    int32_t n_words;      // ceil(n / 32): words of the per-pair pixel bitmap
+    uint32_t* bitmap;     // [batch][n_words], zero on entry
+    int32_t* word_rank;   // [batch][n_words] scratch
     int32_t* pairs;
     int32_t* n_pairs;
 };
 
-// Sort the keys (i << 32 | j) of the converged seeds with a bitonic network, then keep the
-// first of every run: the match set M, ascending in (i, j).
+// Exclusive prefix sum of one int per thread over the block (same contract as
+// block_scan_flag).
+__device__ __forceinline__ int block_scan_int(int value, int* wave_sums, int& total) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, nwaves = (blockDim.x + 63) >> 6;
+    int x = value;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const int y = __shfl_up(x, d);
+        if (lane >= d) x += y;
+    }
+    __syncthreads();
+    if (lane == 63) wave_sums[wave] = x;
+    __syncthreads();
+    int offset = 0, sum = 0;
+    for (int w = 0; w < nwaves; ++w) {
+        const int s = wave_sums[w];
+        if (w < wave) offset += s;
+        sum += s;
+    }
+    total = sum;
+    return offset + x - value;
+}
+
+// The match set M, sorted by (i, j) without duplicates.  A match's j is the nearest
+// neighbour of its i, so two converged seeds with equal i carry equal j and sorting the
+// pairs is sorting their i.  That is done as a distribution sort over the pixel range: mark
+// the i of every converged seed in a bitmap, rank the set bits with a prefix sum of word
+// popcounts, and let every converged seed write its pair at the rank of its i (seeds that
+// share a match write the same value to the same place).
 __global__ __launch_bounds__(STEP_THREADS) void recip_dedup_kernel(DedupArgs a) {
-    extern __shared__ u64 lds_buf[];
     __shared__ int wave_sums[17];
     const int b = blockIdx.x;
     const int64_t base = (int64_t)b * a.n_seeds;
-    u64* buf = a.global_buf ? a.global_buf + (int64_t)b * a.n_sort : lds_buf;
-    const u64 none = ~0ull;
+    uint32_t* bitmap = a.bitmap + (int64_t)b * a.n_words;
+    int32_t* word_rank = a.word_rank + (int64_t)b * a.n_words;
 
-    for (int i = threadIdx.x; i < a.n_sort; i += STEP_THREADS) {
-        u64 k = none;
-        if (i < a.n_seeds && a.seed_iter[base + i] >= 0)
-            k = ((u64)(uint32_t)a.seed_i[base + i] << 32) | (u64)(uint32_t)a.seed_j[base + i];
-        buf[i] = k;
+    for (int s = threadIdx.x; s < a.n_seeds; s += STEP_THREADS) {
+        if (a.seed_iter[base + s] >= 0) {
+            const uint32_t i = (uint32_t)a.seed_i[base + s];
+            atomicOr(&bitmap[i >> 5], 1u << (i & 31));
+        }
     }
     __syncthreads();
-    for (int k = 2; k <= a.n_sort; k <<= 1) {
-        for (int j = k >> 1; j > 0; j >>= 1) {
-            for (int i = threadIdx.x; i < a.n_sort; i += STEP_THREADS) {
-                const int partner = i ^ j;
-                if (partner > i) {
-                    const u64 x = buf[i], y = buf[partner];
-                    const bool ascending = (i & k) == 0;
-                    if ((x > y) == ascending) {
-                        buf[i] = y;
-                        buf[partner] = x;
-                    }
-                }
-            }
-            __syncthreads();
-        }
+
+    // contiguous run of words per thread, so that ranks ascend with the thread index
+    const int per_thread = (a.n_words + STEP_THREADS - 1) / STEP_THREADS;
+    const int w0 = min((int)threadIdx.x * per_thread, a.n_words);
+    const int w1 = min(w0 + per_thread, a.n_words);
+    int mine = 0;
+    for (int w = w0; w < w1; ++w)
+        mine += __popc(__hip_atomic_load(&bitmap[w], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+    int count;
+    int rank = block_scan_int(mine, wave_sums, count);
+    for (int w = w0; w < w1; ++w) {
+        word_rank[w] = rank;
+        rank += __popc(__hip_atomic_load(&bitmap[w], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
     }
-    int count = 0;
-    for (int start = 0; start < a.n_sort; start += STEP_THREADS) {
-        const int i = start + (int)threadIdx.x;
-        u64 k = none;
-        bool first = false;
-        if (i < a.n_sort) {
-            k = buf[i];
-            first = (k != none) && (i == 0 || buf[i - 1] != k);
+    __syncthreads();
+
+    for (int s = threadIdx.x; s < a.n_seeds; s += STEP_THREADS) {
+        if (a.seed_iter[base + s] >= 0) {
+            const uint32_t i = (uint32_t)a.seed_i[base + s];
+            const uint32_t word = __hip_atomic_load(&bitmap[i >> 5], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            const int pos = __hip_atomic_load(&word_rank[i >> 5], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) +
+                            __popc(word & ((1u << (i & 31)) - 1u));
+            a.pairs[(base + pos) * 2 + 0] = (int32_t)i;
+            a.pairs[(base + pos) * 2 + 1] = a.seed_j[base + s];
         }
-        int total;
-        const int pos = count + block_scan_flag(first, wave_sums, total);
-        if (first) {
-            a.pairs[(base + pos) * 2 + 0] = (int32_t)(k >> 32);
-            a.pairs[(base + pos) * 2 + 1] = (int32_t)(k & 0xFFFFFFFFull);
-        }
-        count += total;
     }
     for (int i = count + threadIdx.x; i < a.n_seeds; i += STEP_THREADS) {
         a.pairs[(base + i) * 2 + 0] = -1;
@@ -154,7 +176,8 @@ __global__ __launch_bounds__(STEP_THREADS) void recip_dedup_kernel(DedupArgs a) 
 }
 
 hipError_t launch_recip_init(const RecipState& st, const int32_t* seeds, int32_t n_seeds, int batch, hipStream_t s) {
-    int blocks = (n_seeds + 255) / 256;
+    int64_t most = st.n_words > n_seeds ? st.n_words : n_seeds;
+    int blocks = (int)((most + 255) / 256);
     if (blocks < 1) blocks = 1;
     if (blocks > 256) blocks = 256;
     return launch(TK_RECIP_INIT, recip_init_kernel, dim3(blocks, batch), dim3(256), 0, s, st, seeds, n_seeds);
@@ -187,13 +210,12 @@ hipError_t launch_recip_dedup(const RecipState& st, int32_t n_seeds, int batch,
     a.seed_j = seed_j;
     a.seed_iter = seed_iter;
     a.n_seeds = n_seeds;
-    a.n_sort = (int32_t)st.sort_len;
+    a.n_words = (int32_t)st.n_words;
+    a.bitmap = st.bitmap;
+    a.word_rank = st.word_rank;
     a.pairs = pairs;
     a.n_pairs = n_pairs;
-    const size_t lds_bytes = (size_t)st.sort_len * sizeof(u64);
-    const bool in_lds = lds_bytes <= 48 * 1024;
-    a.global_buf = in_lds ? nullptr : st.sort_buf;
-    return launch(TK_RECIP_DEDUP, recip_dedup_kernel, dim3(batch), dim3(STEP_THREADS), in_lds ? lds_bytes : 0, s, a);
+    return launch(TK_RECIP_DEDUP, recip_dedup_kernel, dim3(batch), dim3(STEP_THREADS), 0, s, a);
 }
 
 }  // namespace fnn

@@ -82,6 +82,16 @@ void search_kernel(SearchArgs a) {
         const int rg = (int)(unit % row_groups);
         const int slot0 = rg * 32 * R;
 
+        const int t0 = chunk * tiles_per_chunk;
+        const int t1 = min(t0 + tiles_per_chunk, a.m_tiles);
+        // P candidate tiles are always in flight towards the registers; a slot is refilled
+        // as soon as its tile has been handed to the matrix cores.  The first P loads are
+        // issued before the (dependent) query fetch so that both latencies overlap.
+        Frag ring[P];
+#pragma unroll
+        for (int p = 0; p < P; ++p)
+            ring[p] = O::load(tgt + ((int64_t)min(t0 + p, t1 - 1) * 32 + c) * O::ROW_BYTES, h);
+
         // blocks past the live queries of the last row group are computed on row 0 and dropped
         Frag q[R];
         float best[R];
@@ -95,14 +105,6 @@ void search_kernel(SearchArgs a) {
             best_tile[r] = 0x7FFFFFFF;
         }
 
-        const int t0 = chunk * tiles_per_chunk;
-        const int t1 = min(t0 + tiles_per_chunk, a.m_tiles);
-        // P candidate tiles are always in flight towards the registers; a slot is refilled
-        // as soon as its tile has been handed to the matrix cores
-        Frag ring[P];
-#pragma unroll
-        for (int p = 0; p < P; ++p)
-            ring[p] = O::load(tgt + ((int64_t)min(t0 + p, t1 - 1) * 32 + c) * O::ROW_BYTES, h);
         for (int tb = t0; tb < t1; tb += P) {
 #pragma unroll
             for (int p = 0; p < P; ++p) {
@@ -198,9 +200,22 @@ void resolve_kernel(SearchArgs a, int32_t* out_idx, float* out_score) {
 
 template <int CT, int DP>
 static hipError_t launch_search_t(const SearchArgs& a, int batch, hipStream_t s) {
-    // enough waves to occupy every SIMD several times over, shared between the pairs
-    int wgs = 2048 / batch;
-    if (wgs < 128) wgs = 128;
+    // One resident wave per hardware slot: the grid is exactly what the chip holds at once
+    // (workgroups per CU from the occupancy calculator x CUs), split evenly between the
+    // pairs, so there is no partial last round and the per-wave start-up cost and the final
+    // key merges are paid once per slot.
+    static int resident_wgs = 0;
+    if (resident_wgs == 0) {
+        int per_cu = 0, dev = 0;
+        hipDeviceProp_t prop;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, search_kernel<CT, DP, SEARCH_R, SEARCH_P>,
+                                                         SEARCH_WAVES * 64, 0) != hipSuccess ||
+            hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess)
+            return hipErrorUnknown;
+        resident_wgs = (per_cu > 0 ? per_cu : 1) * prop.multiProcessorCount;
+    }
+    int wgs = resident_wgs / batch;
+    if (wgs < 1) wgs = 1;
     const int64_t max_units = (int64_t)((a.nq + 32 * SEARCH_R - 1) / (32 * SEARCH_R)) *
                               ((a.m_tiles + SEARCH_MIN_TILES - 1) / SEARCH_MIN_TILES);
     const int64_t need = (max_units + SEARCH_WAVES - 1) / SEARCH_WAVES;
@@ -212,9 +227,11 @@ hipError_t launch_search(const SearchArgs& a, int batch, int compute, int dp, hi
     if (a.nq <= 0 || batch <= 0) return hipSuccess;
     if (compute == FNN_F16) {
         if (dp == 16) return launch_search_t<CT_F16, 16>(a, batch, s);
+        if (dp == 24) return launch_search_t<CT_F16, 24>(a, batch, s);
         if (dp == 32) return launch_search_t<CT_F16, 32>(a, batch, s);
     } else if (compute == FNN_BF16) {
         if (dp == 16) return launch_search_t<CT_BF16, 16>(a, batch, s);
+        if (dp == 24) return launch_search_t<CT_BF16, 24>(a, batch, s);
         if (dp == 32) return launch_search_t<CT_BF16, 32>(a, batch, s);
     } else {
         if (dp == 8) return launch_search_t<CT_F32, 8>(a, batch, s);
@@ -238,9 +255,11 @@ hipError_t launch_resolve(const SearchArgs& a, int batch, int compute, int dp, i
     if (a.nq <= 0 || batch <= 0) return hipSuccess;
     if (compute == FNN_F16) {
         if (dp == 16) return launch_resolve_t<CT_F16, 16>(a, batch, out_idx, out_score, s);
+        if (dp == 24) return launch_resolve_t<CT_F16, 24>(a, batch, out_idx, out_score, s);
         if (dp == 32) return launch_resolve_t<CT_F16, 32>(a, batch, out_idx, out_score, s);
     } else if (compute == FNN_BF16) {
         if (dp == 16) return launch_resolve_t<CT_BF16, 16>(a, batch, out_idx, out_score, s);
+        if (dp == 24) return launch_resolve_t<CT_BF16, 24>(a, batch, out_idx, out_score, s);
         if (dp == 32) return launch_resolve_t<CT_BF16, 32>(a, batch, out_idx, out_score, s);
     } else {
         if (dp == 8) return launch_resolve_t<CT_F32, 8>(a, batch, out_idx, out_score, s);

@@ -18,7 +18,8 @@ enum TraceKind : int {
     TK_DENSE = 7,
     TK_DENSE_FINAL = 8,
     TK_RESOLVE = 9,
-    TK_COUNT = 10
+    TK_DENSE_RESOLVE = 10,
+    TK_COUNT = 11
 };
 
 // Returns false when no trace is open or it is full; otherwise hands out the next event pair.
