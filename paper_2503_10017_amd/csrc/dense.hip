@@ -54,6 +54,15 @@ __device__ __forceinline__ void dense_sweep(const DenseArgs& a, const typename O
     const float ninf = -__builtin_inff();
     Frag qa = O::load(qbase, h);
     Frag qb = O::load(qbase + 32 * O::ROW_BYTES, h);
+    // Software pipeline: the matrix instructions of the NEXT product pair are issued before
+    // the current pair's 32 result registers are folded, so the matrix cores stay busy while
+    // the vector ALU works.
+    // Two buffers used alternately (J is even, so every step starts on buffer 0 again and no
+    // register copies are needed).
+    static_assert(DENSE_J % 2 == 0, "the pipeline alternates two result buffers");
+    f32x16 pa[2], pb[2];
+    pa[0] = O::mma(cand[0], qa);
+    pb[0] = O::mma(cand[0], qb);
     for (int t = 0; t < S; t += 2) {
         // prefetch the next two query blocks (the last step reloads its own)
         const int tn = min(t + 2, S - 2);
@@ -62,26 +71,33 @@ __device__ __forceinline__ void dense_sweep(const DenseArgs& a, const typename O
         float ra = ninf, rb = ninf;
 #pragma unroll
         for (int jt = 0; jt < J; ++jt) {
-            f32x16 xa = O::mma(cand[jt], qa);
-            f32x16 xb = O::mma(cand[jt], qb);
+            const int cur = jt & 1, nxt = cur ^ 1;
+            // next pair: the following resident tile, or tile 0 against the next query blocks
+            // (after the last step that product is computed once more and never folded)
+            if (jt + 1 < J) {
+                pa[nxt] = O::mma(cand[jt + 1], qa);
+                pb[nxt] = O::mma(cand[jt + 1], qb);
+            } else {
+                pa[nxt] = O::mma(cand[0], na);
+                pb[nxt] = O::mma(cand[0], nb);
+            }
             if (TAIL) {
                 const int ia = segment_pixel(sbg, t, c);  // pixel of this lane's query in block t
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
                     const bool cand_ok = (tbase + jt) * 32 + tile_row(v, h) < a.m;
-                    if (!cand_ok || ia >= a.n) xa[v] = ninf;
-                    if (!cand_ok || ia + 1 >= a.n) xb[v] = ninf;
+                    if (!cand_ok || ia >= a.n) pa[cur][v] = ninf;
+                    if (!cand_ok || ia + 1 >= a.n) pb[cur][v] = ninf;
                 }
             }
-            ra = fold16f(ra, xa);
-            rb = fold16f(rb, xb);
+            ra = fold16f(ra, pa[cur]);
+            rb = fold16f(rb, pb[cur]);
 #pragma unroll
-            for (int v = 0; v < 16; ++v) cmax[jt][v] = max3f(cmax[jt][v], xa[v], xb[v]);
+            for (int v = 0; v < 16; ++v) cmax[jt][v] = max3f(cmax[jt][v], pa[cur][v], pb[cur][v]);
         }
-        // best candidate of the two queries over this wave's J tiles -> workgroup table
-        ra = __builtin_fmaxf(ra, __shfl_xor(ra, 32));
-        rb = __builtin_fmaxf(rb, __shfl_xor(rb, 32));
-        const float mine = h ? rb : ra;  // half 0 files block t, half 1 block t+1
+        // best candidate of the two queries over this wave's J tiles -> workgroup table:
+        // lane half 0 files block t, half 1 files block t+1
+        const float mine = cross_half_max(ra, rb);
         if (!TAIL || mine != ninf) atomicMax(&lds_rows[(t + h) * 32 + c], pack_key(mine, unit_row));
         qa = na;
         qb = nb;
@@ -142,22 +158,27 @@ void dense_kernel(DenseArgs a) {
                 dense_sweep<CT, DP, false>(a, cand, cmax, qbase, sbg, tbase, lds_row_keys + sb * S * 32, tbase / J, c, h);
 
             // best query of each resident candidate inside this super-block: reduce the 32
-            // lanes of each half and note the lowest lane that attains the maximum
+            // lanes of each half, note the lowest lane that attains the maximum, and let lane v
+            // of each half file the result of register v (one key, one LDS operation per tile)
 #pragma unroll
             for (int jt = 0; jt < J; ++jt) {
+                float my_top = ninf;
+                int my_lo = 0, my_hi = 0;
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
                     const float x = cmax[jt][v];
-                    float top = x;
-#pragma unroll
-                    for (int mask = 1; mask < 32; mask <<= 1) top = __builtin_fmaxf(top, __shfl_xor(top, mask));
+                    const float top = half_max(x);
                     const u64 hit = __ballot(x == top);
                     const int lane_lo = __ffsll((unsigned long long)(hit & 0xFFFFFFFFull)) - 1;
                     const int lane_hi = __ffsll((unsigned long long)(hit >> 32)) - 1;
-                    const int winner = h ? lane_hi : lane_lo;
-                    if (c == 0 && top != ninf)
-                        atomicMax(&lds_col_keys[jt * 32 + tile_row(v, h)], pack_key(top, sbg * 32 + winner));
+                    if (c == v) {
+                        my_top = top;
+                        my_lo = lane_lo;
+                        my_hi = lane_hi;
+                    }
                 }
+                if (c < 16 && my_top != ninf)
+                    atomicMax(&lds_col_keys[jt * 32 + tile_row(c, h)], pack_key(my_top, sbg * 32 + (h ? my_hi : my_lo)));
             }
         }
 

@@ -22,8 +22,9 @@ enum : int { CT_F32 = 0, CT_F16 = 1, CT_BF16 = 2 };
 // ---------------------------------------------------------------------------------------
 __device__ __forceinline__ uint32_t order_bits(float s) {
     s = s + 0.0f;  // -0 -> +0 so that equal floats have equal keys
-    uint32_t b = __float_as_uint(s);
-    return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
+    const uint32_t b = __float_as_uint(s);
+    // negative: flip every bit; non-negative: set the sign bit
+    return b ^ ((uint32_t)((int32_t)b >> 31) | 0x80000000u);
 }
 __device__ __forceinline__ float unorder_bits(uint32_t o) {
     uint32_t b = (o & 0x80000000u) ? (o & 0x7FFFFFFFu) : ~o;
@@ -136,6 +137,28 @@ template <>
 struct Ops<CT_F16, 24> : OpsHalf24<CT_F16> {};
 template <>
 struct Ops<CT_BF16, 24> : OpsHalf24<CT_BF16> {};
+
+// Cross-lane helpers (pure vector-ALU data movement, no LDS round trip).
+template <int CTRL>
+__device__ __forceinline__ float dpp_move(float x) {
+    return __uint_as_float(__builtin_amdgcn_update_dpp(0u, __float_as_uint(x), CTRL, 0xF, 0xF, true));
+}
+// Maximum over the 32 lanes of each wave half, delivered to every lane of that half.
+__device__ __forceinline__ float half_max(float x) {
+    x = __builtin_fmaxf(x, dpp_move<0xB1>(x));   // quad_perm [1,0,3,2]: lane ^ 1
+    x = __builtin_fmaxf(x, dpp_move<0x4E>(x));   // quad_perm [2,3,0,1]: lane ^ 2
+    x = __builtin_fmaxf(x, dpp_move<0x141>(x));  // row_half_mirror: joins the two quads of 8 lanes
+    x = __builtin_fmaxf(x, dpp_move<0x140>(x));  // row_mirror: joins the two halves of a 16-lane row
+    // the two rows of a half trade places
+    const auto sw = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return __builtin_fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
+}
+// For values a (kept by lanes 0..31) and b (kept by lanes 32..63): lane c gets
+// max(a[c], a[c+32]), lane c+32 gets max(b[c], b[c+32]).
+__device__ __forceinline__ float cross_half_max(float a, float b) {
+    const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(a), __float_as_uint(b), false, false);
+    return __builtin_fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
+}
 
 // Candidate offset inside a tile of result register v for lane half h.
 __device__ __forceinline__ constexpr int tile_row(int v, int h) { return 8 * (v >> 2) + 4 * h + (v & 3); }

@@ -69,6 +69,55 @@ __global__ __launch_bounds__(256) void prep_kernel(PrepArgs a) {
     }
 }
 
+// Fast path: fp32 source whose rows are whole 16-byte vectors and need no channel padding
+// (d == dp).  GROUPS = dp / 8 is a compile-time constant so that the row / group split of the
+// item index costs a multiply, and every thread moves two 16-byte loads into one (16-bit
+// formats) or two (fp32) 16-byte stores.
+template <int GROUPS, int COMPUTE>
+__global__ __launch_bounds__(256) void prep_f32_kernel(PrepArgs a) {
+    const int side_idx = blockIdx.y / a.batch;
+    const int b = blockIdx.y % a.batch;
+    const PrepSide& sd = a.side[side_idx];
+    const uint32_t total = (uint32_t)sd.n_pad * GROUPS;
+    constexpr int ESIZE = (COMPUTE == FNN_F32) ? 4 : 2;
+    char* dst = reinterpret_cast<char*>(sd.dst) + (int64_t)b * sd.n_pad * (GROUPS * 8) * ESIZE;
+    const float* src = reinterpret_cast<const float*>(sd.src[b]);
+    for (uint32_t item = blockIdx.x * blockDim.x + threadIdx.x; item < total; item += gridDim.x * blockDim.x) {
+        const uint32_t row = item / GROUPS;
+        const uint32_t g = item - row * GROUPS;
+        const int64_t pix = sd.segment_major ? slot_pixel(row) : (int64_t)row;
+        float4 lo = make_float4(0.f, 0.f, 0.f, 0.f), hi = lo;
+        if (pix < sd.n) {
+            const float4* p = reinterpret_cast<const float4*>(src + pix * sd.row_stride + g * 8);
+            lo = p[0];
+            hi = p[1];
+        }
+        if (COMPUTE == FNN_F32) {
+            float4* out = reinterpret_cast<float4*>(dst + ((int64_t)item * 8) * 4);
+            out[0] = lo;
+            out[1] = hi;
+        } else {
+            const float v[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+            uint16_t hbits[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) hbits[e] = (COMPUTE == FNN_F16) ? float_to_f16_rne(v[e]) : float_to_bf16_rne(v[e]);
+            uint4 packed;
+            packed.x = hbits[0] | ((uint32_t)hbits[1] << 16);
+            packed.y = hbits[2] | ((uint32_t)hbits[3] << 16);
+            packed.z = hbits[4] | ((uint32_t)hbits[5] << 16);
+            packed.w = hbits[6] | ((uint32_t)hbits[7] << 16);
+            *reinterpret_cast<uint4*>(dst + ((int64_t)item * 8) * 2) = packed;
+        }
+    }
+}
+
+template <int GROUPS>
+static hipError_t launch_prep_fast(const PrepArgs& a, dim3 grid, hipStream_t s) {
+    if (a.compute == FNN_F32) return launch(TK_PREP, prep_f32_kernel<GROUPS, FNN_F32>, grid, dim3(256), 0, s, a);
+    if (a.compute == FNN_F16) return launch(TK_PREP, prep_f32_kernel<GROUPS, FNN_F16>, grid, dim3(256), 0, s, a);
+    return launch(TK_PREP, prep_f32_kernel<GROUPS, FNN_BF16>, grid, dim3(256), 0, s, a);
+}
+
 __global__ __launch_bounds__(256) void fill_u64_kernel(u64* p, int64_t count, u64 value) {
     for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < count; i += (int64_t)gridDim.x * blockDim.x)
         p[i] = value;
@@ -98,6 +147,20 @@ hipError_t launch_prep(const PrepArgs& a, hipStream_t s) {
     int64_t blocks = (most + 255) / 256;
     if (blocks > 4096) blocks = 4096;
     dim3 grid((unsigned)blocks, (unsigned)(a.n_sides * a.batch));
+    bool fast = a.d == a.dp && most < (int64_t)1 << 31;
+    for (int i = 0; i < a.n_sides && fast; ++i) {
+        const PrepSide& sd = a.side[i];
+        fast = sd.dtype == FNN_F32 && sd.row_stride % 4 == 0;
+        for (int b = 0; b < a.batch && fast; ++b) fast = ((uintptr_t)sd.src[b] % 16) == 0;
+    }
+    if (fast) {
+        switch (a.dp / 8) {
+            case 1: return launch_prep_fast<1>(a, grid, s);
+            case 2: return launch_prep_fast<2>(a, grid, s);
+            case 3: return launch_prep_fast<3>(a, grid, s);
+            case 4: return launch_prep_fast<4>(a, grid, s);
+        }
+    }
     return launch(TK_PREP, prep_kernel, grid, dim3(256), 0, s, a);
 }
 
