@@ -58,6 +58,8 @@ def main() -> int:
     ap.add_argument("--no-dense", action="store_true", help="skip the dense mutual-NN leg")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--latency", action="store_true", help="also time a single pair (adds search launches)")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run one plain 256 MiB device copy (reference dispatch for scaling HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build targets ONE MI355X; --gpus must be 1 "
@@ -173,6 +175,23 @@ def main() -> int:
         },
         "input_generation_s": round(gen_s, 1),
     }
+
+    # HBM traffic of the search kernel, measured offline with rocprofv3 byte counters (the
+    # command and the scaling are in profiles/); bench.py itself cannot read those counters
+    traffic_file = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    if os.path.exists(traffic_file) and compute == "f16":
+        with open(traffic_file) as f:
+            traffic = json.load(f)
+        result["roofline"]["traffic"] = traffic.get("search_kernel_bytes_per_launch")
+        result["roofline_hbm"]["traffic"] = traffic.get("search_kernel_bytes_per_launch")
+        result["roofline"]["traffic_source"] = traffic.get("source")
+
+    if args.copy_calibration:
+        src = torch.empty(256 << 20, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     # ---- optional: single-pair latency (configs[1]) ----------------------------------------------
     if args.latency:

@@ -58,9 +58,16 @@ void search_kernel(SearchArgs a) {
     using O = Ops<CT, DP>;
     using Frag = typename O::Frag;
     const int lane = threadIdx.x & 63, c = lane & 31, h = lane >> 5;
-    const int wave = blockIdx.x * SEARCH_WAVES + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    // Workgroups are dealt to the 8 XCDs round-robin by their linear id, and each XCD has
+    // its own L2.  Renumber them so that every XCD owns one contiguous run of (pair, unit)
+    // work: the row groups that sweep the same candidate chunk then share one L2 instead
+    // of fetching the chunk from HBM once per XCD.
+    const int n_wgs = gridDim.x * gridDim.y;
+    int wg = blockIdx.y * gridDim.x + blockIdx.x;
+    if ((n_wgs & 7) == 0) wg = (wg & 7) * (n_wgs >> 3) + (wg >> 3);
+    const int b = wg / gridDim.x;
+    const int wave = (wg % gridDim.x) * SEARCH_WAVES + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int n_waves = gridDim.x * SEARCH_WAVES;
-    const int b = blockIdx.y;
 
     int n_act = a.nq;
     if (a.nq_active) n_act = min(max(a.nq_active[b], 0), a.nq);
@@ -215,6 +222,7 @@ static hipError_t launch_search_t(const SearchArgs& a, int batch, hipStream_t s)
         resident_wgs = (per_cu > 0 ? per_cu : 1) * prop.multiProcessorCount;
     }
     int wgs = resident_wgs / batch;
+    if (wgs >= 8) wgs &= ~7;  // a multiple of 8 per pair keeps the XCD renumbering a bijection
     if (wgs < 1) wgs = 1;
     const int64_t max_units = (int64_t)((a.nq + 32 * SEARCH_R - 1) / (32 * SEARCH_R)) *
                               ((a.m_tiles + SEARCH_MIN_TILES - 1) / SEARCH_MIN_TILES);
