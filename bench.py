@@ -140,6 +140,23 @@ def main() -> int:
     peak = PEAK_FP32 if compute == "f32" else PEAK_MFMA_16BIT
     kernel_ms_per_step = {k: sum(v) / args.steps for k, v in sorted(by_kernel.items())}
 
+    # per-search view: launch i of every step has the same live query count, so average the
+    # i-th search launch over the steps and set it against the roofline that bounds it
+    per_search_rows = []
+    lps = int(round(launches_per_step))
+    for i in range(lps):
+        k_act = int(per_search[i]) if i < len(per_search) else 0
+        if k_act == 0:
+            continue
+        us = sum(search_ms[i::lps]) / max(len(search_ms[i::lps]), 1) * 1e3
+        fl = 2.0 * D * N_PIX * k_act
+        by = BATCH * N_PIX * D * esize + k_act * (D * esize + 8)
+        t_mfma = fl / (peak * 1e12) * 1e6
+        t_hbm = by / (PEAK_HBM * 1e9) * 1e6
+        per_search_rows.append({
+            "queries": k_act, "us": round(us, 1), "TFLOP/s": round(fl / us / 1e6, 1), "GB/s": round(by / us / 1e3, 1),
+            "bound": "mfma" if t_mfma >= t_hbm else "hbm", "frac_of_bound": round(max(t_mfma, t_hbm) / us, 3)})
+
     result = {
         "metric": "FastNN image pairs/sec at 512x384 D=24",
         "value": round(pairs_per_s, 2),
@@ -160,6 +177,7 @@ def main() -> int:
         "matches_per_pair": round(float(n_pairs.mean()), 1),
         "active_queries_per_search": (per_search / BATCH).round(1).tolist(),
         "kernel_ms_per_step": {k: round(v, 4) for k, v in kernel_ms_per_step.items()},
+        "live_searches": per_search_rows,
         "roofline": {
             "kernel": "search_kernel", "bound": "mfma",
             "achieved": round(achieved_tflops, 2), "peak": peak, "unit": "TFLOP/s",
