@@ -59,20 +59,24 @@ NearestLayout carve_nearest(Carver& cv, int batch, int64_t n, int64_t m, int d, 
 struct RecipLayout {
     MapsLayout maps;
     RecipState st;
+    int64_t zero_words;  // 64-bit words from keys_f to the end of the bitmap
 };
 RecipLayout carve_recip(Carver& cv, int batch, int64_t n, int64_t m, int d, int64_t n_seeds, int compute) {
     RecipLayout L;
     L.maps = carve_maps(cv, batch, n, m, d, compute);
     const size_t per = (size_t)batch * n_seeds;
+    // keys_f, keys_b and the bitmap are adjacent so that one range clears all three
+    const size_t z0 = cv.used;
     L.st.keys_f = (u64*)cv.take(per * sizeof(u64));
     L.st.keys_b = (u64*)cv.take(per * sizeof(u64));
+    L.st.n_words = (n + 31) / 32;
+    L.st.bitmap = (uint32_t*)cv.take((size_t)batch * L.st.n_words * sizeof(uint32_t));
+    L.zero_words = (int64_t)((cv.used - z0) / sizeof(u64));
     L.st.cur_u[0] = (int32_t*)cv.take(per * sizeof(int32_t));
     L.st.cur_u[1] = (int32_t*)cv.take(per * sizeof(int32_t));
     L.st.seed_id[0] = (int32_t*)cv.take(per * sizeof(int32_t));
     L.st.seed_id[1] = (int32_t*)cv.take(per * sizeof(int32_t));
     L.st.n_active = (int32_t*)cv.take((size_t)batch * sizeof(int32_t));
-    L.st.n_words = (n + 31) / 32;
-    L.st.bitmap = (uint32_t*)cv.take((size_t)batch * L.st.n_words * sizeof(uint32_t));
     L.st.word_rank = (int32_t*)cv.take((size_t)batch * L.st.n_words * sizeof(int32_t));
     return L;
 }
@@ -141,9 +145,10 @@ void fill_prep_side(PrepSide& sd, int32_t batch, const fnn_map* maps, int64_t n_
 }
 
 hipError_t prep_both(int32_t batch, const fnn_map* a, const fnn_map* b, const MapsLayout& L, int d, int compute,
-                     hipStream_t s, bool first_segment_major = false) {
+                     hipStream_t s, const PrepExtra& extra, bool first_segment_major = false) {
     PrepArgs pa;
     memset(&pa, 0, sizeof(pa));
+    pa.extra = extra;
     fill_prep_side(pa.side[0], batch, a, L.n_pad, L.p1);
     pa.side[0].segment_major = first_segment_major ? 1 : 0;
     fill_prep_side(pa.side[1], batch, b, L.m_pad, L.p2);
@@ -224,8 +229,11 @@ int32_t fnn_nearest(int32_t batch, const fnn_map* src, const int32_t* q_idx, int
     if (st != FNN_OK) return st;
     hipStream_t s = (hipStream_t)stream;
 
-    FNN_TRY(prep_both(batch, src, tgt, L.maps, d, opts->compute, s));
-    FNN_TRY(launch_fill_u64(L.keys, (int64_t)batch * nq, 0, s));
+    PrepExtra extra;
+    memset(&extra, 0, sizeof(extra));
+    extra.zero_ptr = L.keys;  // the key table starts empty
+    extra.zero_count = (int64_t)batch * nq;
+    FNN_TRY(prep_both(batch, src, tgt, L.maps, d, opts->compute, s, extra));
     SearchArgs sa;
     memset(&sa, 0, sizeof(sa));
     sa.src = (const char*)L.maps.p1;
@@ -277,8 +285,17 @@ int32_t fnn_reciprocal(int32_t batch, const fnn_map* d1, const fnn_map* d2, cons
         return FNN_OK;
     }
 
-    FNN_TRY(prep_both(batch, d1, d2, L.maps, d, compute, s));
-    FNN_TRY(launch_recip_init(L.st, seeds, ns, batch, s));
+    // the prepare launch also clears the key tables and the sort bitmap and sets U^0 = seeds
+    PrepExtra extra;
+    memset(&extra, 0, sizeof(extra));
+    extra.zero_ptr = L.st.keys_f;
+    extra.zero_count = L.zero_words;
+    extra.seeds = seeds;
+    extra.cur_u = L.st.cur_u[0];
+    extra.seed_id = L.st.seed_id[0];
+    extra.n_active = L.st.n_active;
+    extra.n_seeds = ns;
+    FNN_TRY(prep_both(batch, d1, d2, L.maps, d, compute, s, extra));
 
     SearchArgs fwd;  // queries in image 1 -> candidates in image 2
     memset(&fwd, 0, sizeof(fwd));
@@ -352,8 +369,11 @@ int32_t fnn_mutual_dense(int32_t batch, const fnn_map* d1, const fnn_map* d2, co
     if (st != FNN_OK) return st;
     hipStream_t s = (hipStream_t)stream;
 
-    if (n > 0 && m > 0) FNN_TRY(prep_both(batch, d1, d2, L.maps, d, opts->compute, s, true));
-    FNN_TRY(launch_fill_u64(L.row_keys, (int64_t)batch * (n + m), 0, s));
+    PrepExtra extra;
+    memset(&extra, 0, sizeof(extra));
+    extra.zero_ptr = L.row_keys;  // both key tables start empty
+    extra.zero_count = (int64_t)batch * (n + m);
+    if (n > 0 && m > 0) FNN_TRY(prep_both(batch, d1, d2, L.maps, d, opts->compute, s, extra, true));
 
     DenseArgs da;
     memset(&da, 0, sizeof(da));

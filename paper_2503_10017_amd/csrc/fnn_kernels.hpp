@@ -30,7 +30,19 @@ struct PrepSide {
     int32_t dtype;                   // source storage format
     void* dst;                       // [batch][n_pad][dp] in the compute format
 };
+// Small initialisations that ride along with the prepare launch instead of costing launches
+// of their own: clearing key tables / bitmaps, and step 1 of the FastNN iteration (U^0).
+struct PrepExtra {
+    u64* zero_ptr;          // range of 64-bit words to clear (NULL: none)
+    int64_t zero_count;
+    const int32_t* seeds;   // [batch][n_seeds] (NULL: no seed initialisation)
+    int32_t* cur_u;         // [batch][n_seeds] <- seeds
+    int32_t* seed_id;       // [batch][n_seeds] <- 0, 1, 2, ...
+    int32_t* n_active;      // [batch] <- n_seeds
+    int32_t n_seeds;
+};
 struct PrepArgs {
+    PrepExtra extra;
     PrepSide side[2];
     int32_t n_sides;  // 1 or 2
     int32_t batch;
@@ -76,7 +88,6 @@ struct RecipState {
     int32_t* word_rank;  // [batch][n_words] rank of the first bit of each bitmap word
     int64_t n_words;
 };
-hipError_t launch_recip_init(const RecipState& st, const int32_t* seeds, int32_t n_seeds, int batch, hipStream_t s);
 // mode 0: ordinary iteration t; 1: last iteration (survivors are reported as unconverged);
 // 2: no iteration at all (max_iter == 0): every seed is reported unconverged with (U^0, V^0).
 hipError_t launch_recip_step(const RecipState& st, int which, int32_t n_seeds, int batch, int t, int mode,

@@ -29,8 +29,26 @@ __device__ __forceinline__ uint16_t float_to_f16_rne(float f) {
     return __builtin_bit_cast(uint16_t, hf);
 }
 
+// Side jobs spread over all threads of the launch (see PrepExtra).
+__device__ __forceinline__ void prep_side_jobs(const PrepArgs& a) {
+    const PrepExtra& x = a.extra;
+    const int64_t tid = ((int64_t)blockIdx.y * gridDim.x + blockIdx.x) * blockDim.x + threadIdx.x;
+    const int64_t n_threads = (int64_t)gridDim.x * gridDim.y * blockDim.x;
+    if (x.zero_ptr)
+        for (int64_t i = tid; i < x.zero_count; i += n_threads) x.zero_ptr[i] = 0;
+    if (x.seeds) {
+        const int64_t total = (int64_t)a.batch * x.n_seeds;
+        for (int64_t i = tid; i < total; i += n_threads) {
+            x.cur_u[i] = x.seeds[i];
+            x.seed_id[i] = (int32_t)(i % x.n_seeds);
+        }
+        for (int64_t b = tid; b < a.batch; b += n_threads) x.n_active[b] = x.n_seeds;
+    }
+}
+
 // One thread produces 8 consecutive channels of one output row.
 __global__ __launch_bounds__(256) void prep_kernel(PrepArgs a) {
+    prep_side_jobs(a);
     const int side_idx = blockIdx.y / a.batch;
     const int b = blockIdx.y % a.batch;
     const PrepSide& sd = a.side[side_idx];
@@ -75,6 +93,7 @@ __global__ __launch_bounds__(256) void prep_kernel(PrepArgs a) {
 // formats) or two (fp32) 16-byte stores.
 template <int GROUPS, int COMPUTE>
 __global__ __launch_bounds__(256) void prep_f32_kernel(PrepArgs a) {
+    prep_side_jobs(a);
     const int side_idx = blockIdx.y / a.batch;
     const int b = blockIdx.y % a.batch;
     const PrepSide& sd = a.side[side_idx];

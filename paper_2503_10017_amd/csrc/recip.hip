@@ -11,20 +11,6 @@ namespace fnn {
 
 constexpr int STEP_THREADS = 1024;
 
-__global__ __launch_bounds__(256) void recip_init_kernel(RecipState st, const int32_t* seeds, int32_t n_seeds) {
-    const int b = blockIdx.y;
-    const int64_t base = (int64_t)b * n_seeds;
-    for (int64_t w = blockIdx.x * blockDim.x + threadIdx.x; w < st.n_words; w += gridDim.x * blockDim.x)
-        st.bitmap[(int64_t)b * st.n_words + w] = 0;
-    for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < n_seeds; i += gridDim.x * blockDim.x) {
-        st.cur_u[0][base + i] = seeds[base + i];
-        st.seed_id[0][base + i] = i;
-        st.keys_f[base + i] = 0;
-        st.keys_b[base + i] = 0;
-    }
-    if (blockIdx.x == 0 && threadIdx.x == 0) st.n_active[b] = n_seeds;
-}
-
 struct StepArgs {
     const int32_t* cur_u;     // U^t per slot
     const int32_t* seed_id;
@@ -173,14 +159,6 @@ __global__ __launch_bounds__(STEP_THREADS) void recip_dedup_kernel(DedupArgs a) 
         a.pairs[(base + i) * 2 + 1] = -1;
     }
     if (threadIdx.x == 0) a.n_pairs[b] = count;
-}
-
-hipError_t launch_recip_init(const RecipState& st, const int32_t* seeds, int32_t n_seeds, int batch, hipStream_t s) {
-    int64_t most = st.n_words > n_seeds ? st.n_words : n_seeds;
-    int blocks = (int)((most + 255) / 256);
-    if (blocks < 1) blocks = 1;
-    if (blocks > 256) blocks = 256;
-    return launch(TK_RECIP_INIT, recip_init_kernel, dim3(blocks, batch), dim3(256), 0, s, st, seeds, n_seeds);
 }
 
 hipError_t launch_recip_step(const RecipState& st, int which, int32_t n_seeds, int batch, int t, int mode,
