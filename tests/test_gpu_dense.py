@@ -88,3 +88,21 @@ def test_empty_sides():
     out = fnn.fnn_mutual_dense(dev(a), torch.zeros((0, 24), device=dev(a).device), compute="f16")
     torch.cuda.synchronize()
     assert int(out["n_pairs"][0]) == 0 and np.all(host(out["nn12"]) == -1)
+
+
+def test_strided_half_storage_and_nearest_agreement():
+    # bf16 storage with a row stride (generic prepare path); the dense row table must also
+    # equal what fnn_nearest returns for every pixel as a query (same arithmetic, other kernel)
+    a, b = exact_maps(17, 2300, 4500, 24)
+    wide_a = torch.zeros((2300, 32), dtype=torch.bfloat16, device=dev(a).device)
+    wide_b = torch.zeros((4500, 32), dtype=torch.bfloat16, device=dev(a).device)
+    wide_a[:, :24] = dev(a).to(torch.bfloat16)
+    wide_b[:, :24] = dev(b).to(torch.bfloat16)
+    out = fnn.fnn_mutual_dense(wide_a[:, :24], wide_b[:, :24], compute="bf16")
+    gi, gs = fnn.fnn_nearest(wide_a[:, :24], wide_b[:, :24], compute="bf16")
+    gj, _ = fnn.fnn_nearest(wide_b[:, :24], wide_a[:, :24], compute="bf16")
+    torch.cuda.synchronize()
+    ref = oracle.mutual_dense(a, b)
+    check_exact({k: host(v) for k, v in out.items()}, 0, ref)
+    assert np.array_equal(host(gi)[0], ref["nn12"]) and np.array_equal(host(gs)[0], ref["s12"])
+    assert np.array_equal(host(gj)[0], ref["nn21"])

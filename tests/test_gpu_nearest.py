@@ -107,3 +107,30 @@ def test_repeated_calls_are_deterministic():
     for _ in range(3):
         again = [host(x) for x in fnn.fnn_nearest(ta, tb, compute="f16")]
         assert np.array_equal(first[0], again[0]) and np.array_equal(first[1], again[1])
+
+
+def test_more_queries_than_resident_units_and_side_stream():
+    # every pixel a query (rows groups outnumber the waves of the grid, so waves loop over units),
+    # issued on a non-default stream
+    a, b = exact_maps(21, 20000, 3000, 24)
+    ri, rb, _ = oracle.nearest(a, b)
+    stream = torch.cuda.Stream()
+    ta, tb = dev(a), dev(b)
+    torch.cuda.synchronize()
+    with torch.cuda.stream(stream):
+        gi, gs = fnn.fnn_nearest(ta, tb, compute="bf16", stream=stream)
+    stream.synchronize()
+    assert np.array_equal(host(gi)[0], ri) and np.array_equal(host(gs)[0], rb)
+
+
+def test_maximum_batch_of_small_pairs():
+    batch = 64
+    maps = [exact_maps(500 + b, 130, 70, 24) for b in range(batch)]
+    gi, gs = fnn.fnn_nearest([dev(m[0]) for m in maps], [dev(m[1]) for m in maps], compute="f16")
+    torch.cuda.synchronize()
+    gi, gs = host(gi), host(gs)
+    for b in range(batch):
+        ri, rb, _ = oracle.nearest(*maps[b])
+        assert np.array_equal(gi[b], ri) and np.array_equal(gs[b], rb)
+    with pytest.raises(fnn.FnnError):
+        fnn.fnn_nearest([dev(m[0]) for m in maps] + [dev(maps[0][0])], [dev(m[1]) for m in maps] + [dev(maps[0][1])])

@@ -96,3 +96,27 @@ def test_gaussian_pair_pinned_seeds(compute):
     if compute != "bf16":
         ref = oracle.reciprocal(a, b, seeds, 10)
         check_reciprocal_pinned(got, 0, ref, a, b, GAP_F32 if compute == "f32" else GAP_HALF, f"{compute} fp32 inputs")
+
+
+def test_many_iterations_and_strided_half_storage():
+    # long iteration cap (the launch sequence keeps going after every seed has converged) and
+    # fp16 maps stored with a row stride, which takes the generic prepare path
+    a, b = synth.exact_pair(91, 56, 40, 24)
+    seeds = synth.grid_seeds(56, 40, 3)
+    ref = oracle.reciprocal(a, b, seeds, 40)
+    wide_a = torch.zeros((a.shape[0], 36), dtype=torch.float16, device=dev(a).device)
+    wide_b = torch.zeros((b.shape[0], 36), dtype=torch.float16, device=dev(a).device)
+    wide_a[:, :24] = dev(a).to(torch.float16)
+    wide_b[:, :24] = dev(b).to(torch.float16)
+    out = fnn.fnn_reciprocal(wide_a[:, :24], wide_b[:, :24], dev(seeds)[None], max_iter=40, compute="f16")
+    torch.cuda.synchronize()
+    check_reciprocal_exact({k: host(v) for k, v in out.items()}, 0, ref)
+
+
+def test_batch_of_64_pairs():
+    pairs = [synth.exact_pair(700 + b, 24, 20, 24) for b in range(64)]
+    rng = np.random.default_rng(3)
+    seeds = rng.integers(0, 480, size=(64, 50)).astype(np.int32)
+    got = run_reciprocal([p[0] for p in pairs], [p[1] for p in pairs], seeds, 10, "bf16")
+    for b in range(64):
+        check_reciprocal_exact(got, b, oracle.reciprocal(pairs[b][0], pairs[b][1], seeds[b], 10))
