@@ -75,10 +75,20 @@ typedef struct {
     int64_t row_stride;   /* in elements */
 } fnn_map;
 
+/*
+ * FNN_FLAG_NORMALIZE: the maps are raw matching-head outputs (section 3.1.4, "Matching Head");
+ * every descriptor is divided by its Euclidean norm before the cast to the compute format:
+ * norm2 = sum_k x[k]*x[k] in fp32 (k ascending, products and sums rounded separately),
+ * y[k] = x[k] / sqrt(norm2) with correctly rounded fp32 sqrt and division; an all-zero
+ * descriptor stays zero.  The step is fused into the prepare pass.
+ */
+#define FNN_FLAG_NORMALIZE 1
+
 typedef struct {
     int32_t compute;      /* fnn_dtype the products are formed in (see above) */
     int32_t max_iter;     /* fnn_reciprocal only: T, the iteration cap (>= 0) */
-    int32_t reserved[6];  /* must be zero */
+    int32_t flags;        /* bitwise OR of FNN_FLAG_* */
+    int32_t reserved[5];  /* must be zero */
 } fnn_opts;
 
 /* Human-readable name of a status code (static storage). */

@@ -11,6 +11,8 @@ What each function follows:
 * ``mutual_dense``  -- the "traditional mutual nearest neighbour" definition the paper
                        contrasts FastNN with (section 3.2, "Problem Context"): a pair
                        (i, j) is kept when j is i's best candidate and i is j's.
+* ``normalize``     -- the producer step in front of the search: the matching head's maps
+                       (section 3.1.4) L2-normalised per pixel, in fp32.
 * ``reciprocal``    -- the FastNN iteration (section 3.2, "FastNN Algorithm", steps 1-4),
                        step by step: U^0 = seeds, V^0 = NN_2(U^0); each iteration
                        U^{t+1} = NN_1(V^t), matches M_t are the seeds with
@@ -50,6 +52,8 @@ def _load():
             ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32,
             ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
         ]
+        lib.oracle_normalize.restype = None
+        lib.oracle_normalize.argtypes = [ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32, ctypes.c_void_p]
         lib.oracle_threads.restype = ctypes.c_int32
         lib.oracle_threads.argtypes = []
         _lib = lib
@@ -72,6 +76,14 @@ def round_bf16(x: np.ndarray) -> np.ndarray:
     u = u + np.uint64(0x7FFF) + ((u >> np.uint64(16)) & np.uint64(1))
     u = (u & np.uint64(0xFFFF0000)).astype(np.uint32)
     return u.view(np.float32).reshape(np.shape(x))
+
+
+def normalize(x: np.ndarray) -> np.ndarray:
+    """Every row divided by its Euclidean norm, in fp32 as the library's normalise option defines it."""
+    x = np.ascontiguousarray(x, dtype=np.float32)
+    y = np.empty_like(x)
+    _load().oracle_normalize(x.ctypes.data, x.shape[0], x.shape[1], y.ctypes.data)
+    return y
 
 
 def nearest(a: np.ndarray, b: np.ndarray):

@@ -55,6 +55,27 @@ void oracle_nearest(const float* a, int64_t k_rows, const float* b, int64_t m_ro
     }
 }
 
+/*
+ * The producer step in front of the search (paper section 3.1.4, "Matching Head": the maps
+ * D1, D2 come out of the head un-normalised): every descriptor divided by its Euclidean norm.
+ * norm2 = sum_k x[k]*x[k] in fp32, k ascending, every product and every sum rounded on its
+ * own; y[k] = x[k] / sqrtf(norm2) (IEEE sqrt and division); an all-zero descriptor stays zero.
+ */
+void oracle_normalize(const float* x, int64_t rows, int32_t d, float* y)
+{
+    for (int64_t r = 0; r < rows; ++r) {
+        const float* xr = x + r * (int64_t)d;
+        float* yr = y + r * (int64_t)d;
+        float norm2 = 0.0f;
+        for (int32_t k = 0; k < d; ++k) {
+            float sq = xr[k] * xr[k];
+            norm2 = norm2 + sq;
+        }
+        float norm = sqrtf(norm2);
+        for (int32_t k = 0; k < d; ++k) yr[k] = norm > 0.0f ? xr[k] / norm : xr[k];
+    }
+}
+
 /* Number of threads the parallel loop above uses (for the benchmark's report). */
 #ifdef _OPENMP
 #include <omp.h>

@@ -33,7 +33,8 @@ class _Map(ctypes.Structure):
 
 
 class _Opts(ctypes.Structure):
-    _fields_ = [("compute", ctypes.c_int32), ("max_iter", ctypes.c_int32), ("reserved", ctypes.c_int32 * 6)]
+    _fields_ = [("compute", ctypes.c_int32), ("max_iter", ctypes.c_int32), ("flags", ctypes.c_int32),
+                ("reserved", ctypes.c_int32 * 5)]
 
 
 def library_path() -> str:
@@ -109,10 +110,14 @@ def _map_array(views):
     return arr
 
 
-def _opts(compute, max_iter=0):
+FNN_FLAG_NORMALIZE = 1
+
+
+def _opts(compute, max_iter=0, normalize=False):
     o = _Opts()
     o.compute = _COMPUTE[compute]
     o.max_iter = int(max_iter)
+    o.flags = FNN_FLAG_NORMALIZE if normalize else 0
     return o
 
 
@@ -139,7 +144,8 @@ def _workspace(workspace, need, device):
 def fnn_nearest(src: MapsLike, tgt: MapsLike, q_idx: Optional[torch.Tensor] = None,
                 nq: Optional[int] = None, nq_active: Optional[torch.Tensor] = None, compute="f16",
                 out_idx: Optional[torch.Tensor] = None, out_score: Optional[torch.Tensor] = None,
-                want_score: bool = True, workspace: Optional[torch.Tensor] = None, stream=None):
+                want_score: bool = True, normalize: bool = False, workspace: Optional[torch.Tensor] = None,
+                stream=None):
     """One-directional search; returns (out_idx int32[batch][nq], out_score float32[batch][nq] or None)."""
     lib = load_library()
     sv, tv = _as_pairs(src), _as_pairs(tgt)
@@ -153,7 +159,7 @@ def fnn_nearest(src: MapsLike, tgt: MapsLike, q_idx: Optional[torch.Tensor] = No
         out_score = torch.empty((batch, nq), dtype=torch.float32, device=device)
     need = fnn_workspace_bytes(batch, sv[0].shape[0], tv[0].shape[0], sv[0].shape[1], nq, compute)
     workspace = _workspace(workspace, need, device)
-    o = _opts(compute)
+    o = _opts(compute, normalize=normalize)
     sa, ta = _map_array(sv), _map_array(tv)
     st = lib.fnn_nearest(batch, ctypes.cast(sa, ctypes.c_void_p), _ptr(q_idx), nq, _ptr(nq_active),
                          ctypes.cast(ta, ctypes.c_void_p), ctypes.byref(o), _ptr(out_idx), _ptr(out_score),
@@ -164,7 +170,8 @@ def fnn_nearest(src: MapsLike, tgt: MapsLike, q_idx: Optional[torch.Tensor] = No
 
 
 def fnn_reciprocal(d1: MapsLike, d2: MapsLike, seeds: torch.Tensor, max_iter: int = 10, compute="f16",
-                   out: Optional[dict] = None, workspace: Optional[torch.Tensor] = None, stream=None):
+                   out: Optional[dict] = None, normalize: bool = False, workspace: Optional[torch.Tensor] = None,
+                   stream=None):
     """The FastNN iteration; returns a dict of device tensors
     seed_i, seed_j, seed_iter [batch][n_seeds], pairs [batch][n_seeds][2], n_pairs [batch]."""
     lib = load_library()
@@ -182,7 +189,7 @@ def fnn_reciprocal(d1: MapsLike, d2: MapsLike, seeds: torch.Tensor, max_iter: in
         }
     need = fnn_workspace_bytes(batch, v1[0].shape[0], v2[0].shape[0], v1[0].shape[1], n_seeds, compute)
     workspace = _workspace(workspace, need, device)
-    o = _opts(compute, max_iter)
+    o = _opts(compute, max_iter, normalize)
     a1, a2 = _map_array(v1), _map_array(v2)
     st = lib.fnn_reciprocal(batch, ctypes.cast(a1, ctypes.c_void_p), ctypes.cast(a2, ctypes.c_void_p),
                             _ptr(seeds), n_seeds, ctypes.byref(o),
@@ -195,7 +202,7 @@ def fnn_reciprocal(d1: MapsLike, d2: MapsLike, seeds: torch.Tensor, max_iter: in
 
 
 def fnn_mutual_dense(d1: MapsLike, d2: MapsLike, compute="f16", out: Optional[dict] = None,
-                     workspace: Optional[torch.Tensor] = None, stream=None):
+                     normalize: bool = False, workspace: Optional[torch.Tensor] = None, stream=None):
     """All-pairs mutual nearest neighbours; returns a dict of device tensors
     nn12, s12 [batch][n], nn21, s21 [batch][m], pairs [batch][min(n,m)][2], n_pairs [batch]."""
     lib = load_library()
@@ -214,7 +221,7 @@ def fnn_mutual_dense(d1: MapsLike, d2: MapsLike, compute="f16", out: Optional[di
         }
     need = fnn_workspace_bytes(batch, n, m, v1[0].shape[1], 0, compute)
     workspace = _workspace(workspace, need, device)
-    o = _opts(compute)
+    o = _opts(compute, normalize=normalize)
     a1, a2 = _map_array(v1), _map_array(v2)
     st = lib.fnn_mutual_dense(batch, ctypes.cast(a1, ctypes.c_void_p), ctypes.cast(a2, ctypes.c_void_p),
                               ctypes.byref(o), _ptr(out["nn12"]), _ptr(out.get("s12")), _ptr(out["nn21"]),

@@ -123,7 +123,8 @@ int32_t check_opts(const fnn_opts* o) {
     if (!o) return FNN_E_NULL;
     if (!valid_dtype(o->compute)) return FNN_E_DTYPE;
     if (o->max_iter < 0) return FNN_E_RANGE;
-    for (int i = 0; i < 6; ++i)
+    if (o->flags & ~FNN_FLAG_NORMALIZE) return FNN_E_RANGE;
+    for (int i = 0; i < 5; ++i)
         if (o->reserved[i] != 0) return FNN_E_RANGE;
     return FNN_OK;
 }
@@ -144,8 +145,9 @@ void fill_prep_side(PrepSide& sd, int32_t batch, const fnn_map* maps, int64_t n_
     sd.dst = dst;
 }
 
-hipError_t prep_both(int32_t batch, const fnn_map* a, const fnn_map* b, const MapsLayout& L, int d, int compute,
+hipError_t prep_both(int32_t batch, const fnn_map* a, const fnn_map* b, const MapsLayout& L, int d, const fnn_opts* opts,
                      hipStream_t s, const PrepExtra& extra, bool first_segment_major = false) {
+    const int compute = opts->compute;
     PrepArgs pa;
     memset(&pa, 0, sizeof(pa));
     pa.extra = extra;
@@ -157,6 +159,7 @@ hipError_t prep_both(int32_t batch, const fnn_map* a, const fnn_map* b, const Ma
     pa.d = d;
     pa.dp = L.dp;
     pa.compute = compute;
+    pa.normalize = (opts->flags & FNN_FLAG_NORMALIZE) ? 1 : 0;
     return launch_prep(pa, s);
 }
 
@@ -233,7 +236,7 @@ int32_t fnn_nearest(int32_t batch, const fnn_map* src, const int32_t* q_idx, int
     memset(&extra, 0, sizeof(extra));
     extra.zero_ptr = L.keys;  // the key table starts empty
     extra.zero_count = (int64_t)batch * nq;
-    FNN_TRY(prep_both(batch, src, tgt, L.maps, d, opts->compute, s, extra));
+    FNN_TRY(prep_both(batch, src, tgt, L.maps, d, opts, s, extra));
     SearchArgs sa;
     memset(&sa, 0, sizeof(sa));
     sa.src = (const char*)L.maps.p1;
@@ -295,7 +298,7 @@ int32_t fnn_reciprocal(int32_t batch, const fnn_map* d1, const fnn_map* d2, cons
     extra.seed_id = L.st.seed_id[0];
     extra.n_active = L.st.n_active;
     extra.n_seeds = ns;
-    FNN_TRY(prep_both(batch, d1, d2, L.maps, d, compute, s, extra));
+    FNN_TRY(prep_both(batch, d1, d2, L.maps, d, opts, s, extra));
 
     SearchArgs fwd;  // queries in image 1 -> candidates in image 2
     memset(&fwd, 0, sizeof(fwd));
@@ -373,7 +376,7 @@ int32_t fnn_mutual_dense(int32_t batch, const fnn_map* d1, const fnn_map* d2, co
     memset(&extra, 0, sizeof(extra));
     extra.zero_ptr = L.row_keys;  // both key tables start empty
     extra.zero_count = (int64_t)batch * (n + m);
-    if (n > 0 && m > 0) FNN_TRY(prep_both(batch, d1, d2, L.maps, d, opts->compute, s, extra, true));
+    if (n > 0 && m > 0) FNN_TRY(prep_both(batch, d1, d2, L.maps, d, opts, s, extra, true));
 
     DenseArgs da;
     memset(&da, 0, sizeof(da));

@@ -49,6 +49,7 @@ struct PrepArgs {
     int32_t d;
     int32_t dp;
     int32_t compute;
+    int32_t normalize;  // divide every descriptor by its Euclidean norm first (FNN_FLAG_NORMALIZE)
 };
 hipError_t launch_prep(const PrepArgs& a, hipStream_t s);
 hipError_t launch_fill_u64(u64* p, int64_t count, u64 value, hipStream_t s);

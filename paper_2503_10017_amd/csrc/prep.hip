@@ -29,6 +29,17 @@ __device__ __forceinline__ uint16_t float_to_f16_rne(float f) {
     return __builtin_bit_cast(uint16_t, hf);
 }
 
+// Euclidean norm of one source descriptor as FNN_FLAG_NORMALIZE defines it: squares and
+// sums rounded separately (no fused multiply-add), channels in ascending order.
+__device__ __forceinline__ float descriptor_norm(const void* src, int64_t first, int d, int dtype) {
+    float sum = 0.0f;
+    for (int k = 0; k < d; ++k) {
+        const float x = load_as_float(src, first + k, dtype);
+        sum = __fadd_rn(sum, __fmul_rn(x, x));
+    }
+    return __fsqrt_rn(sum);
+}
+
 // Side jobs spread over all threads of the launch (see PrepExtra).
 __device__ __forceinline__ void prep_side_jobs(const PrepArgs& a) {
     const PrepExtra& x = a.extra;
@@ -67,6 +78,13 @@ __global__ __launch_bounds__(256) void prep_kernel(PrepArgs a) {
         for (int e = 0; e < 8; ++e) {
             const int k = g * 8 + e;
             v[e] = (pix < sd.n && k < a.d) ? load_as_float(src, pix * sd.row_stride + k, sd.dtype) : 0.0f;
+        }
+        if (a.normalize && pix < sd.n) {
+            const float norm = descriptor_norm(src, pix * sd.row_stride, a.d, sd.dtype);
+            if (norm > 0.0f) {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) v[e] = __fdiv_rn(v[e], norm);
+            }
         }
         if (a.compute == FNN_F32) {
             float4* out = reinterpret_cast<float4*>(dst + (row * a.dp + g * 8) * 4);
@@ -110,6 +128,13 @@ __global__ __launch_bounds__(256) void prep_f32_kernel(PrepArgs a) {
             const float4* p = reinterpret_cast<const float4*>(src + pix * sd.row_stride + g * 8);
             lo = p[0];
             hi = p[1];
+            if (a.normalize) {
+                const float norm = descriptor_norm(src, pix * sd.row_stride, a.d, FNN_F32);
+                if (norm > 0.0f) {
+                    lo = make_float4(__fdiv_rn(lo.x, norm), __fdiv_rn(lo.y, norm), __fdiv_rn(lo.z, norm), __fdiv_rn(lo.w, norm));
+                    hi = make_float4(__fdiv_rn(hi.x, norm), __fdiv_rn(hi.y, norm), __fdiv_rn(hi.z, norm), __fdiv_rn(hi.w, norm));
+                }
+            }
         }
         if (COMPUTE == FNN_F32) {
             float4* out = reinterpret_cast<float4*>(dst + ((int64_t)item * 8) * 4);

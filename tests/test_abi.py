@@ -47,7 +47,7 @@ def test_workspace_bytes(lib):
     big = fnn.fnn_workspace_bytes(1, 196608, 196608, 24, 3072, "f16")
     batch = fnn.fnn_workspace_bytes(16, 196608, 196608, 24, 3072, "f16")
     assert 0 < small < big < batch
-    assert big >= 2 * 196608 * 32 * 2                      # two prepared 16-bit maps
+    assert big >= 2 * 196608 * 24 * 2                      # two prepared 16-bit maps, 24 channels unpadded
     assert fnn.fnn_workspace_bytes(1, 196608, 196608, 24, 3072, "f32") > big
     assert fnn.fnn_workspace_bytes(0, 10, 10, 24, 1, "f16") == 0     # batch out of range
     assert fnn.fnn_workspace_bytes(1, 10, 10, 33, 1, "f16") == 0     # d out of range
@@ -65,10 +65,11 @@ def _map(n=64, d=24, dtype=0, stride=None, data=0x1000):
     return arr
 
 
-def _opts(compute=1, max_iter=10, reserved0=0):
+def _opts(compute=1, max_iter=10, reserved0=0, flags=0):
     o = binding._Opts()
     o.compute = compute
     o.max_iter = max_iter
+    o.flags = flags
     o.reserved[0] = reserved0
     return o
 
@@ -99,6 +100,7 @@ def test_argument_errors_are_caught_on_the_host(lib):
     assert _nearest(lib, ok_map, ok_map, _opts(compute=5)) == 3
     assert _nearest(lib, ok_map, ok_map, _opts(max_iter=-1)) == 4      # FNN_E_RANGE
     assert _nearest(lib, ok_map, ok_map, _opts(reserved0=1)) == 4
+    assert _nearest(lib, ok_map, ok_map, _opts(flags=2)) == 4          # unknown flag
     assert _nearest(lib, ok_map, ok_map, opts, ws=0) == 5              # FNN_E_WORKSPACE
     assert _nearest(lib, ok_map, ok_map, opts, ws=0x10001) == 5        # misaligned
     assert _nearest(lib, ok_map, ok_map, opts, ws_bytes=16) == 5       # too small

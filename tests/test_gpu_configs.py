@@ -73,6 +73,10 @@ def _check_dense_sampled(a, b, compute, n_sample, seed):
     assert n_pairs == int(keep.sum())
     assert np.array_equal(got["pairs"][:n_pairs], np.stack([i[keep], nn12[keep]], axis=1))
     assert np.all(got["pairs"][n_pairs:] == -1)
+    # a mutual pair's score is computed twice, by the two resolve passes with the operands in
+    # swapped roles (query replicated / candidate replicated): the bits must agree
+    mi, mj = got["pairs"][:n_pairs, 0], got["pairs"][:n_pairs, 1]
+    assert np.array_equal(got["s12"][mi], got["s21"][mj])
     # the score tables are consistent with the index tables (recomputed in float64)
     s = np.einsum("nd,nd->n", ra[rows].astype(np.float64), rb[nn12[rows]].astype(np.float64))
     assert np.all(np.abs(s - got["s12"][rows]) <= 1e-5)

@@ -134,3 +134,29 @@ def test_maximum_batch_of_small_pairs():
         assert np.array_equal(gi[b], ri) and np.array_equal(gs[b], rb)
     with pytest.raises(fnn.FnnError):
         fnn.fnn_nearest([dev(m[0]) for m in maps] + [dev(maps[0][0])], [dev(m[1]) for m in maps] + [dev(maps[0][1])])
+
+
+@pytest.mark.parametrize("compute", COMPUTES)
+def test_fused_normalisation(compute):
+    # raw (un-normalised) head outputs: the prepare pass normalises, casts and pads in one go;
+    # the oracle normalises in fp32 the same way, then rounds like the compute format
+    from gpu_helpers import GAP_ROUNDED, ROUNDERS, SCORE_TOL_ROUNDED, check_nearest_against
+    rng = np.random.default_rng(77)
+    a = (rng.standard_normal((700, 24)) * rng.uniform(0.05, 20.0, size=(700, 1))).astype(np.float32)
+    b = (rng.standard_normal((9000, 24)) * rng.uniform(0.05, 20.0, size=(9000, 1))).astype(np.float32)
+    a[13] = 0.0                                            # an all-zero descriptor stays zero
+    gi, gs = fnn.fnn_nearest(dev(a), dev(b), compute=compute, normalize=True)
+    torch.cuda.synchronize()
+    rnd = ROUNDERS[compute]
+    ri, rb, rs = oracle.nearest(rnd(oracle.normalize(a)), rnd(oracle.normalize(b)))
+    clear = check_nearest_against(host(gi)[0], host(gs)[0], ri, rb, rs, GAP_ROUNDED, SCORE_TOL_ROUNDED, compute)
+    assert clear.mean() > 0.95
+    assert host(gs)[0][13] == 0.0
+    # strided fp16 storage goes through the generic prepare path
+    wide = torch.zeros((9000, 40), dtype=torch.float16, device=dev(b).device)
+    wide[:, :24] = dev(b).to(torch.float16)
+    b16 = host(wide[:, :24].float())
+    gi, gs = fnn.fnn_nearest(dev(a), wide[:, :24], compute=compute, normalize=True)
+    torch.cuda.synchronize()
+    ri, rb, rs = oracle.nearest(rnd(oracle.normalize(a)), rnd(oracle.normalize(b16)))
+    check_nearest_against(host(gi)[0], host(gs)[0], ri, rb, rs, GAP_ROUNDED, SCORE_TOL_ROUNDED, compute + " strided")

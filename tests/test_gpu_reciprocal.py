@@ -120,3 +120,22 @@ def test_batch_of_64_pairs():
     got = run_reciprocal([p[0] for p in pairs], [p[1] for p in pairs], seeds, 10, "bf16")
     for b in range(64):
         check_reciprocal_exact(got, b, oracle.reciprocal(pairs[b][0], pairs[b][1], seeds[b], 10))
+
+
+def test_fused_normalisation_reciprocal_and_dense():
+    rng = np.random.default_rng(5)
+    a, b, _ = synth.warped_pair(61, 96, 64, 24)
+    a = (a * rng.uniform(0.1, 9.0, size=(a.shape[0], 1))).astype(np.float32)     # undo the unit norms
+    b = (b * rng.uniform(0.1, 9.0, size=(b.shape[0], 1))).astype(np.float32)
+    seeds = synth.grid_seeds(96, 64, 4)
+    out = fnn.fnn_reciprocal(dev(a), dev(b), dev(seeds)[None], max_iter=10, compute="f16", normalize=True)
+    dense = fnn.fnn_mutual_dense(dev(a), dev(b), compute="f16", normalize=True)
+    torch.cuda.synchronize()
+    ra, rb = oracle.round_fp16(oracle.normalize(a)), oracle.round_fp16(oracle.normalize(b))
+    ref = oracle.reciprocal(ra, rb, seeds, 10)
+    check_reciprocal_pinned({k: host(v) for k, v in out.items()}, 0, ref, ra, rb, GAP_ROUNDED, "normalised")
+    dref = oracle.mutual_dense(ra, rb)
+    clear = dref["gap12"] > GAP_ROUNDED
+    assert np.array_equal(host(dense["nn12"])[0][clear], dref["nn12"][clear])
+    clear = dref["gap21"] > GAP_ROUNDED
+    assert np.array_equal(host(dense["nn21"])[0][clear], dref["nn21"][clear])

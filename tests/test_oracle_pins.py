@@ -360,3 +360,26 @@ def test_generator_shapes_and_determinism():
     assert np.all(np.abs(w[:, 1] - c[1]) <= 0.15 * 48 + 1e-9)
     assert synth.grid_seeds(512, 384, 8).shape == (3072,)
     assert synth.grid_seeds(512, 384, 8)[65] == 8 * 512 + 8
+
+
+# ------------------------------------------------------------------------------ normalise
+def test_normalize_closed_forms_and_invariants():
+    x = np.array([[3.0, 4.0], [0.0, 0.0], [-5.0, 12.0], [1.0, 0.0]], dtype=np.float32)
+    y = oracle.normalize(x)
+    assert np.array_equal(y[0], np.array([3.0, 4.0], dtype=np.float32) / np.float32(5.0))
+    assert np.array_equal(y[1], [0.0, 0.0])                       # an all-zero descriptor stays zero
+    assert np.array_equal(y[2], np.array([-5.0, 12.0], dtype=np.float32) / np.float32(13.0))
+    assert np.array_equal(y[3], [1.0, 0.0])
+    rng = np.random.default_rng(12)
+    z = (rng.standard_normal((2000, 24)) * rng.uniform(0.01, 50.0, size=(2000, 1))).astype(np.float32)
+    yz = oracle.normalize(z)
+    z64 = z.astype(np.float64)
+    want = z64 / np.linalg.norm(z64, axis=1, keepdims=True)
+    assert np.max(np.abs(yz - want)) < 3e-7                       # a few fp32 roundings at most
+    assert np.allclose(np.linalg.norm(yz.astype(np.float64), axis=1), 1.0, atol=3e-7)
+    # scaling by a power of two commutes with every rounding: bit-identical result
+    assert np.array_equal(oracle.normalize(z * np.float32(8.0)), yz)
+    assert np.array_equal(oracle.normalize(z * np.float32(0.25)), yz)
+    # the sign pattern and the ordering of channels survive
+    assert np.array_equal(np.sign(yz), np.sign(z))
+    assert np.array_equal(np.argmax(np.abs(yz), axis=1), np.argmax(np.abs(z), axis=1))
