@@ -168,8 +168,10 @@ def main() -> int:
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": {"f16": "f16 products, f32 accumulate/select", "bf16": "bf16 products, f32 accumulate/select",
-                  "f32": "f32"}[compute],
+        "dtype": compute,
+        "dtype_detail": {"f16": "descriptors rounded to f16, products exact in f32, f32 accumulation and selection",
+                         "bf16": "descriptors rounded to bf16, products exact in f32, f32 accumulation and selection",
+                         "f32": "f32 throughout"}[compute],
         "data": "synthetic",
         "config": {"workload": "configs[3]: 16 pairs 512x384 D=24 fp32 maps, FastNN reciprocal, subsample 8 "
                                "(3072 seeds/pair), max_iter 10, batched in one call", "batch": BATCH,
