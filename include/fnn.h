@@ -32,6 +32,9 @@
  *    256-byte aligned).  All work is enqueued on `stream` (a hipStream_t, NULL = default
  *    stream) and the call returns without waiting; outputs are valid once the stream has
  *    reached that point.  Two calls that share a workspace must be ordered by the stream.
+ *    A call may be captured into a HIP graph (it launches kernels only, clears its buffers with
+ *    kernels and never synchronises) once the same entry point has run eagerly on the device,
+ *    which fills the launch-shape caches.
  *  - Errors are return codes only.  Argument errors are detected on the host before
  *    anything is enqueued (outputs untouched).  Index arrays live in device memory and are
  *    NOT range-checked: a seed or query index outside [0, n) is undefined behaviour.

@@ -139,3 +139,35 @@ def test_fused_normalisation_reciprocal_and_dense():
     assert np.array_equal(host(dense["nn12"])[0][clear], dref["nn12"][clear])
     clear = dref["gap21"] > GAP_ROUNDED
     assert np.array_equal(host(dense["nn21"])[0][clear], dref["nn21"][clear])
+
+
+def test_hip_graph_capture_and_replay():
+    # the call sequence allocates nothing, never synchronises and clears its buffers with
+    # kernels, so it can be captured into a HIP graph; every replay must equal the eager result
+    a, b, _ = synth.warped_pair(83, 128, 96, 24)
+    seeds = dev(synth.grid_seeds(128, 96, 4))[None]
+    ta, tb = dev(a), dev(b)
+    ws = torch.empty(fnn.fnn_workspace_bytes(1, a.shape[0], b.shape[0], 24, seeds.shape[1], "f16"),
+                     dtype=torch.uint8, device=ta.device)
+    eager = fnn.fnn_reciprocal(ta, tb, seeds, max_iter=10, compute="f16", workspace=ws)   # also warms the launch caches
+    torch.cuda.synchronize()
+    want = {k: host(v).copy() for k, v in eager.items()}
+    out = {k: torch.zeros_like(v) for k, v in eager.items()}
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            fnn.fnn_reciprocal(ta, tb, seeds, max_iter=10, compute="f16", out=out, workspace=ws, stream=side)
+    torch.cuda.synchronize()
+    for rep in range(3):
+        for v in out.values():
+            v.fill_(-5)                                   # eager work between the replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for k in want:
+            assert np.array_equal(host(out[k]), want[k]), (rep, k)
+        again = fnn.fnn_reciprocal(ta, tb, seeds, max_iter=10, compute="f16", workspace=ws)
+        torch.cuda.synchronize()
+        for k in want:
+            assert np.array_equal(host(again[k]), want[k]), (rep, k, "eager")
