@@ -58,6 +58,8 @@ def main() -> int:
     ap.add_argument("--no-dense", action="store_true", help="skip the dense mutual-NN leg")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--latency", action="store_true", help="also time a single pair (adds search launches)")
+    ap.add_argument("--contrast", action="store_true",
+                    help="also time the paper's blocked schedules (Algorithms 1 and 2 with a materialised score block)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 256 MiB device copy (reference dispatch for scaling HBM byte counters)")
     args = ap.parse_args()
@@ -225,6 +227,42 @@ def main() -> int:
             fnn.fnn_reciprocal(ta, tb, ts, MAX_ITER, compute, out=o1, workspace=ws)
         torch.cuda.synchronize()
         result["single_pair_ms"] = round((time.perf_counter() - t0) / 50 * 1e3, 4)
+
+    # ---- optional: the paper's schedules against the fused search, first search of one pair --------
+    if args.contrast:
+        a, b = synth.config_pair(2)
+        ta, tb = torch.from_numpy(a).to(dev), torch.from_numpy(b).to(dev)
+        q = seeds[0].contiguous()
+        rows = 1024
+
+        def timed(fn, reps):
+            fn()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(reps):
+                fn()
+            torch.cuda.synchronize()
+            return (time.perf_counter() - t0) / reps * 1e3
+
+        lib = fnn.load_library()
+        need1 = int(lib.fnn_blocked_workspace_bytes(N_PIX, N_PIX, D, rows, 0, 1))
+        need2 = int(lib.fnn_blocked_workspace_bytes(N_PIX, N_PIX, D, rows, rows, 1))
+        cws = torch.empty(max(need1, need2), dtype=torch.uint8, device=dev)
+        fused_ms = timed(lambda: fnn.fnn_nearest(ta, tb, q_idx=q[None], compute="f16", workspace=ws), 20)
+        single_ms = timed(lambda: fnn.fnn_nearest_blocked(ta, tb, rows, 0, q_idx=q, compute="f16", workspace=cws), 5)
+        double_ms = timed(lambda: fnn.fnn_nearest_blocked(ta, tb, rows, rows, q_idx=q, compute="f16", workspace=cws), 2)
+        score_bytes = float(n_seeds) * N_PIX * 4
+        result["schedule_contrast"] = {
+            "workload": "one search of configs[1]: 3072 grid queries of image 1 against the 196608 pixels of image 2, "
+                        "f16 products; every variant includes the prepare pass",
+            "fused_ms": round(fused_ms, 4),
+            "single_loop_ms": round(single_ms, 4), "double_loop_ms": round(double_ms, 4), "block_size": rows,
+            "score_block_bytes_written_and_read": 2 * score_bytes,
+            "fused_bytes": float(N_PIX) * D * 2 + n_seeds * (D * 2 + 8),
+            "note": "single loop = Algorithm 2 (FastNN-Lite), double loop = Algorithm 1; both materialise the scores in HBM "
+                    "and launch two kernels per block; the fused search keeps them in registers",
+        }
+        del cws
 
     # ---- dense all-pairs mutual NN on one 512x384 pair (configs[2]), fp16 ------------------------
     if not args.no_dense:

@@ -155,6 +155,24 @@ int32_t fnn_mutual_dense(int32_t batch, const fnn_map* d1, const fnn_map* d2, co
                          void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * The paper's own search schedules, for comparison with fnn_nearest (same results, one image
+ * pair): block_cols == 0 runs Algorithm 2 ("FastNN-Lite", section 3.4.3): a single loop over
+ * blocks of block_rows queries, each scored against the WHOLE candidate map into a
+ * block_rows x m block of fp32 scores in the workspace, followed by a selection kernel;
+ * block_cols > 0 runs Algorithm 1 ("Original FastNN"): the double loop over blocks of
+ * block_rows queries and block_cols candidates with the strict "<" running update.  Every
+ * loop trip is two host-launched kernels and the score block goes through device memory --
+ * the traffic the fused search avoids.  block_rows >= 1; block_cols is rounded up to a
+ * multiple of 32.  out_score is required.  Workspace: fnn_blocked_workspace_bytes().
+ */
+size_t fnn_blocked_workspace_bytes(int64_t n, int64_t m, int32_t d, int32_t block_rows, int32_t block_cols,
+                                   int32_t compute);
+int32_t fnn_nearest_blocked(const fnn_map* src, const int32_t* q_idx, int64_t nq, const fnn_map* tgt,
+                            const fnn_opts* opts, int32_t block_rows, int32_t block_cols,
+                            int32_t* out_idx, float* out_score,
+                            void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * Measurement aid (not part of the paper's method; used by the benchmark).  Between
  * fnn_trace_begin and fnn_trace_end every kernel the library launches -- up to max_kernels,
  * later ones run untimed -- carries its own pair of HIP events, so that fnn_trace_end can

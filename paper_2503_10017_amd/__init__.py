@@ -11,6 +11,7 @@ from .binding import (  # noqa: F401
     FnnError,
     fnn_mutual_dense,
     fnn_nearest,
+    fnn_nearest_blocked,
     fnn_reciprocal,
     fnn_status_string,
     fnn_trace_begin,

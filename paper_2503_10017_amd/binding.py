@@ -61,6 +61,10 @@ def load_library():
     lib.fnn_reciprocal.argtypes = [i32, vp, vp, vp, i64, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.fnn_mutual_dense.restype = i32
     lib.fnn_mutual_dense.argtypes = [i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.fnn_blocked_workspace_bytes.restype = sz
+    lib.fnn_blocked_workspace_bytes.argtypes = [i64, i64, i32, i32, i32, i32]
+    lib.fnn_nearest_blocked.restype = i32
+    lib.fnn_nearest_blocked.argtypes = [vp, vp, i64, vp, vp, i32, i32, vp, vp, vp, sz, vp]
     lib.fnn_trace_begin.restype = i32
     lib.fnn_trace_begin.argtypes = [i32]
     lib.fnn_trace_end.restype = i32
@@ -230,6 +234,29 @@ def fnn_mutual_dense(d1: MapsLike, d2: MapsLike, compute="f16", out: Optional[di
     if st != 0:
         raise FnnError(st, "fnn_mutual_dense")
     return out
+
+
+def fnn_nearest_blocked(src: torch.Tensor, tgt: torch.Tensor, block_rows: int, block_cols: int = 0,
+                        q_idx: Optional[torch.Tensor] = None, compute="f16", normalize: bool = False,
+                        workspace: Optional[torch.Tensor] = None, stream=None):
+    """The paper's blocked schedules (block_cols == 0: single loop, else double loop) on one pair;
+    returns (out_idx int32[nq], out_score float32[nq])."""
+    lib = load_library()
+    device = src.device
+    nq = q_idx.shape[-1] if q_idx is not None else src.shape[0]
+    out_idx = torch.empty((nq,), dtype=torch.int32, device=device)
+    out_score = torch.empty((nq,), dtype=torch.float32, device=device)
+    need = int(lib.fnn_blocked_workspace_bytes(src.shape[0], tgt.shape[0], src.shape[1], block_rows, block_cols,
+                                               _COMPUTE[compute]))
+    workspace = _workspace(workspace, need, device)
+    o = _opts(compute, normalize=normalize)
+    sa, ta = _map_array([src]), _map_array([tgt])
+    st = lib.fnn_nearest_blocked(ctypes.cast(sa, ctypes.c_void_p), _ptr(q_idx), nq, ctypes.cast(ta, ctypes.c_void_p),
+                                 ctypes.byref(o), block_rows, block_cols, _ptr(out_idx), _ptr(out_score),
+                                 _ptr(workspace), workspace.numel(), _stream_ptr(stream, device))
+    if st != 0:
+        raise FnnError(st, "fnn_nearest_blocked")
+    return out_idx, out_score
 
 
 def fnn_trace_begin(max_kernels: int = 4096) -> None:

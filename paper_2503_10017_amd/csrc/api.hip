@@ -255,6 +255,63 @@ int32_t fnn_nearest(int32_t batch, const fnn_map* src, const int32_t* q_idx, int
     return FNN_OK;
 }
 
+size_t fnn_blocked_workspace_bytes(int64_t n, int64_t m, int32_t d, int32_t block_rows, int32_t block_cols,
+                                   int32_t compute) {
+    if (!shape_ok(1, n, m, d, 0) || !valid_dtype(compute) || block_rows < 1 || block_cols < 0) return 0;
+    Carver cv{nullptr, 0};
+    carve_maps(cv, 1, n, m, d, compute);
+    const int64_t ld = block_cols > 0 ? round_up(block_cols, 32) : round_up(m, 32);
+    cv.take((size_t)block_rows * ld * sizeof(float));
+    return cv.used + WS_ALIGN;
+}
+
+int32_t fnn_nearest_blocked(const fnn_map* src, const int32_t* q_idx, int64_t nq, const fnn_map* tgt,
+                            const fnn_opts* opts, int32_t block_rows, int32_t block_cols, int32_t* out_idx,
+                            float* out_score, void* workspace, size_t workspace_bytes, void* stream) {
+    int32_t st = check_maps(1, src);
+    if (st != FNN_OK) return st;
+    st = check_maps(1, tgt);
+    if (st != FNN_OK) return st;
+    st = check_opts(opts);
+    if (st != FNN_OK) return st;
+    const int64_t n = src[0].n, m = tgt[0].n;
+    const int32_t d = src[0].d;
+    if (tgt[0].d != d || nq < 0 || nq > MAX_PIXELS || block_rows < 1 || block_cols < 0) return FNN_E_SHAPE;
+    if ((!q_idx && nq > n) || (nq > 0 && n == 0)) return FNN_E_SHAPE;
+    if (nq > 0 && (!out_idx || !out_score)) return FNN_E_NULL;
+    if (nq == 0) return FNN_OK;
+
+    Carver cv{(char*)workspace, 0};
+    MapsLayout L = carve_maps(cv, 1, n, m, d, opts->compute);
+    const int64_t ld = block_cols > 0 ? round_up(block_cols, 32) : round_up(m, 32);
+    float* dists = (float*)cv.take((size_t)block_rows * ld * sizeof(float));
+    st = check_workspace(workspace, workspace_bytes, cv.used);
+    if (st != FNN_OK) return st;
+    hipStream_t s = (hipStream_t)stream;
+
+    PrepExtra extra;
+    memset(&extra, 0, sizeof(extra));
+    FNN_TRY(prep_both(1, src, tgt, L, d, opts, s, extra));
+    if (m == 0) {
+        FNN_TRY(launch_fill_i32f32(out_idx, out_score, nq, s));
+        return FNN_OK;
+    }
+    BlockedArgs ba;
+    memset(&ba, 0, sizeof(ba));
+    ba.src = (const char*)L.p1;
+    ba.src_rows = (int32_t)L.n_pad;
+    ba.q_idx = q_idx;
+    ba.nq = (int32_t)nq;
+    ba.tgt = (const char*)L.p2;
+    ba.m = (int32_t)m;
+    ba.dists = dists;
+    ba.ld = ld;
+    ba.out_idx = out_idx;
+    ba.out_score = out_score;
+    FNN_TRY(run_blocked(ba, opts->compute, L.dp, block_rows, (int)(block_cols > 0 ? ld : 0), s));
+    return FNN_OK;
+}
+
 int32_t fnn_reciprocal(int32_t batch, const fnn_map* d1, const fnn_map* d2, const int32_t* seeds, int64_t n_seeds,
                        const fnn_opts* opts, int32_t* seed_i, int32_t* seed_j, int32_t* seed_iter, int32_t* pairs,
                        int32_t* n_pairs, void* workspace, size_t workspace_bytes, void* stream) {

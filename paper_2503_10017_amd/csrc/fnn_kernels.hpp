@@ -78,6 +78,22 @@ hipError_t launch_search(const SearchArgs& a, int batch, int compute, int dp, hi
 hipError_t launch_resolve(const SearchArgs& a, int batch, int compute, int dp, int32_t* out_idx, float* out_score,
                           hipStream_t s);
 
+// ---- the paper's blocked schedules with a materialised score block (contrast experiment) ----
+struct BlockedArgs {
+    const char* src;        // prepared query map (one pair)
+    int32_t src_rows;
+    const int32_t* q_idx;   // [nq] or NULL
+    int32_t nq;
+    const char* tgt;        // prepared candidate map
+    int32_t m;
+    float* dists;           // [block_rows][ld] score block in device memory
+    int64_t ld;             // columns of the score block (multiple of 32)
+    int32_t* out_idx;       // [nq]
+    float* out_score;       // [nq] (required: it holds the running best between blocks)
+};
+// block_cols == 0: Algorithm 2 (whole B per block of A); otherwise Algorithm 1 (double loop).
+hipError_t run_blocked(const BlockedArgs& a, int compute, int dp, int block_rows, int block_cols, hipStream_t s);
+
 // ---- reciprocal iteration bookkeeping ----------------------------------------------------
 struct RecipState {
     int32_t* cur_u[2];   // [batch][n_seeds] ping-pong: U^t of the seeds still moving

@@ -90,6 +90,7 @@ const char* fnn_trace_kind_name(int32_t kind) {
         case TK_DENSE_FINAL: return "dense_final_kernels";
         case TK_RESOLVE: return "resolve_kernel";
         case TK_DENSE_RESOLVE: return "dense_resolve_kernels";
+        case TK_BLOCKED: return "blocked_kernels";
         default: return "unknown";
     }
 }

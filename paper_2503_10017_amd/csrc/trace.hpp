@@ -19,7 +19,8 @@ enum TraceKind : int {
     TK_DENSE_FINAL = 8,
     TK_RESOLVE = 9,
     TK_DENSE_RESOLVE = 10,
-    TK_COUNT = 11
+    TK_BLOCKED = 11,
+    TK_COUNT = 12
 };
 
 // Returns false when no trace is open or it is full; otherwise hands out the next event pair.

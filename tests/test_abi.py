@@ -29,8 +29,9 @@ def declared_functions():
 
 def test_every_declared_symbol_is_exported(lib):
     names = declared_functions()
-    assert names == ["fnn_mutual_dense", "fnn_nearest", "fnn_reciprocal", "fnn_status_string", "fnn_trace_begin",
-                     "fnn_trace_end", "fnn_trace_kind_name", "fnn_workspace_bytes"]
+    assert names == ["fnn_blocked_workspace_bytes", "fnn_mutual_dense", "fnn_nearest", "fnn_nearest_blocked",
+                     "fnn_reciprocal", "fnn_status_string", "fnn_trace_begin", "fnn_trace_end", "fnn_trace_kind_name",
+                     "fnn_workspace_bytes"]
     for name in names:
         assert hasattr(lib, name), name
 
