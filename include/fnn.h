@@ -86,6 +86,14 @@ typedef struct {
  * descriptor stays zero.  The step is fused into the prepare pass.
  */
 #define FNN_FLAG_NORMALIZE 1
+/*
+ * FNN_FLAG_HALF_ACCUMULATE (fnn_nearest_blocked with compute == FNN_F16 only; the other
+ * entry points answer FNN_E_UNSUPPORTED): the negative control of section 3.4.4 ("if one
+ * naively uses only FP16 ..."): every product is rounded to fp16 and the sum is accumulated
+ * in fp16, k ascending (IEEE binary16 multiply and add, no fused multiply-add); only the
+ * selection stays in fp32.  Exists to measure how many nearest neighbours that changes.
+ */
+#define FNN_FLAG_HALF_ACCUMULATE 2
 
 typedef struct {
     int32_t compute;      /* fnn_dtype the products are formed in (see above) */

@@ -13,6 +13,7 @@ What each function follows:
                        (i, j) is kept when j is i's best candidate and i is j's.
 * ``normalize``     -- the producer step in front of the search: the matching head's maps
                        (section 3.1.4) L2-normalised per pixel, in fp32.
+* ``nearest_half_accumulate`` -- the "naive FP16 only" negative control of section 3.4.4.
 * ``reciprocal``    -- the FastNN iteration (section 3.2, "FastNN Algorithm", steps 1-4),
                        step by step: U^0 = seeds, V^0 = NN_2(U^0); each iteration
                        U^{t+1} = NN_1(V^t), matches M_t are the seeds with
@@ -103,6 +104,25 @@ def nearest(a: np.ndarray, b: np.ndarray):
     _load().oracle_nearest(a.ctypes.data, k, b.ctypes.data, m, d,
                            idx.ctypes.data, best.ctypes.data, second.ctypes.data)
     return idx, best, second
+
+
+def nearest_half_accumulate(a: np.ndarray, b: np.ndarray):
+    """The "naive FP16 only" control of the paper's HybridCast section (3.4.4): inputs rounded to
+    fp16, every product rounded to fp16, the sum accumulated in fp16 (k ascending, multiply and
+    add rounded separately); the selection (lowest index of the largest score) as in ``nearest``.
+
+    numpy's float16 arithmetic rounds each operation once to binary16, which is what is meant.
+    Returns (idx int32[K], best float32[K]).  O(K*M) memory: small inputs only.
+    """
+    a16 = np.asarray(a, dtype=np.float32).astype(np.float16)
+    b16 = np.asarray(b, dtype=np.float32).astype(np.float16)
+    acc = np.zeros((a16.shape[0], b16.shape[0]), dtype=np.float16)
+    for k in range(a16.shape[1]):
+        prod = a16[:, k][:, None] * b16[:, k][None, :]          # float16 * float16 -> float16
+        acc = acc + prod                                          # float16 + float16 -> float16
+    scores = acc.astype(np.float32)
+    idx = np.argmax(scores, axis=1).astype(np.int32)              # first maximum = lowest index
+    return idx, scores[np.arange(scores.shape[0]), idx]
 
 
 def mutual_dense(d1: np.ndarray, d2: np.ndarray):

@@ -115,13 +115,14 @@ def _map_array(views):
 
 
 FNN_FLAG_NORMALIZE = 1
+FNN_FLAG_HALF_ACCUMULATE = 2
 
 
-def _opts(compute, max_iter=0, normalize=False):
+def _opts(compute, max_iter=0, normalize=False, half_accumulate=False):
     o = _Opts()
     o.compute = _COMPUTE[compute]
     o.max_iter = int(max_iter)
-    o.flags = FNN_FLAG_NORMALIZE if normalize else 0
+    o.flags = (FNN_FLAG_NORMALIZE if normalize else 0) | (FNN_FLAG_HALF_ACCUMULATE if half_accumulate else 0)
     return o
 
 
@@ -238,7 +239,7 @@ def fnn_mutual_dense(d1: MapsLike, d2: MapsLike, compute="f16", out: Optional[di
 
 def fnn_nearest_blocked(src: torch.Tensor, tgt: torch.Tensor, block_rows: int, block_cols: int = 0,
                         q_idx: Optional[torch.Tensor] = None, compute="f16", normalize: bool = False,
-                        workspace: Optional[torch.Tensor] = None, stream=None):
+                        half_accumulate: bool = False, workspace: Optional[torch.Tensor] = None, stream=None):
     """The paper's blocked schedules (block_cols == 0: single loop, else double loop) on one pair;
     returns (out_idx int32[nq], out_score float32[nq])."""
     lib = load_library()
@@ -249,7 +250,7 @@ def fnn_nearest_blocked(src: torch.Tensor, tgt: torch.Tensor, block_rows: int, b
     need = int(lib.fnn_blocked_workspace_bytes(src.shape[0], tgt.shape[0], src.shape[1], block_rows, block_cols,
                                                _COMPUTE[compute]))
     workspace = _workspace(workspace, need, device)
-    o = _opts(compute, normalize=normalize)
+    o = _opts(compute, normalize=normalize, half_accumulate=half_accumulate)
     sa, ta = _map_array([src]), _map_array([tgt])
     st = lib.fnn_nearest_blocked(ctypes.cast(sa, ctypes.c_void_p), _ptr(q_idx), nq, ctypes.cast(ta, ctypes.c_void_p),
                                  ctypes.byref(o), block_rows, block_cols, _ptr(out_idx), _ptr(out_score),

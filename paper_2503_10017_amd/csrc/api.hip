@@ -123,7 +123,7 @@ int32_t check_opts(const fnn_opts* o) {
     if (!o) return FNN_E_NULL;
     if (!valid_dtype(o->compute)) return FNN_E_DTYPE;
     if (o->max_iter < 0) return FNN_E_RANGE;
-    if (o->flags & ~FNN_FLAG_NORMALIZE) return FNN_E_RANGE;
+    if (o->flags & ~(FNN_FLAG_NORMALIZE | FNN_FLAG_HALF_ACCUMULATE)) return FNN_E_RANGE;
     for (int i = 0; i < 5; ++i)
         if (o->reserved[i] != 0) return FNN_E_RANGE;
     return FNN_OK;
@@ -218,6 +218,7 @@ int32_t fnn_nearest(int32_t batch, const fnn_map* src, const int32_t* q_idx, int
     if (st != FNN_OK) return st;
     st = check_opts(opts);
     if (st != FNN_OK) return st;
+    if (opts->flags & FNN_FLAG_HALF_ACCUMULATE) return FNN_E_UNSUPPORTED;
     const int64_t n = src[0].n, m = tgt[0].n;
     const int32_t d = src[0].d;
     if (tgt[0].d != d || nq < 0 || nq > MAX_PIXELS) return FNN_E_SHAPE;
@@ -274,6 +275,7 @@ int32_t fnn_nearest_blocked(const fnn_map* src, const int32_t* q_idx, int64_t nq
     if (st != FNN_OK) return st;
     st = check_opts(opts);
     if (st != FNN_OK) return st;
+    if ((opts->flags & FNN_FLAG_HALF_ACCUMULATE) && opts->compute != FNN_F16) return FNN_E_UNSUPPORTED;
     const int64_t n = src[0].n, m = tgt[0].n;
     const int32_t d = src[0].d;
     if (tgt[0].d != d || nq < 0 || nq > MAX_PIXELS || block_rows < 1 || block_cols < 0) return FNN_E_SHAPE;
@@ -308,7 +310,8 @@ int32_t fnn_nearest_blocked(const fnn_map* src, const int32_t* q_idx, int64_t nq
     ba.ld = ld;
     ba.out_idx = out_idx;
     ba.out_score = out_score;
-    FNN_TRY(run_blocked(ba, opts->compute, L.dp, block_rows, (int)(block_cols > 0 ? ld : 0), s));
+    ba.half_accumulate = (opts->flags & FNN_FLAG_HALF_ACCUMULATE) ? 1 : 0;
+    FNN_TRY(run_blocked(ba, opts->compute, d, L.dp, block_rows, (int)(block_cols > 0 ? ld : 0), s));
     return FNN_OK;
 }
 
@@ -322,6 +325,7 @@ int32_t fnn_reciprocal(int32_t batch, const fnn_map* d1, const fnn_map* d2, cons
     if (st != FNN_OK) return st;
     st = check_opts(opts);
     if (st != FNN_OK) return st;
+    if (opts->flags & FNN_FLAG_HALF_ACCUMULATE) return FNN_E_UNSUPPORTED;
     const int64_t n = d1[0].n, m = d2[0].n;
     const int32_t d = d1[0].d;
     if (d2[0].d != d || n_seeds < 0 || n_seeds > MAX_PIXELS) return FNN_E_SHAPE;
@@ -416,6 +420,7 @@ int32_t fnn_mutual_dense(int32_t batch, const fnn_map* d1, const fnn_map* d2, co
     if (st != FNN_OK) return st;
     st = check_opts(opts);
     if (st != FNN_OK) return st;
+    if (opts->flags & FNN_FLAG_HALF_ACCUMULATE) return FNN_E_UNSUPPORTED;
     const int64_t n = d1[0].n, m = d2[0].n;
     const int32_t d = d1[0].d;
     if (d2[0].d != d) return FNN_E_SHAPE;

@@ -5,6 +5,8 @@
 // to memory, a second kernel selects from it -- the way a tensor framework runs them.  The
 // results are identical to the fused search; only the schedule and the memory traffic differ
 // (section 3.4.3, Figure 2: block accesses (P/BS)^2 versus P/BS).
+#include <hip/hip_fp16.h>
+
 #include "fnn_device.hpp"
 #include "fnn_kernels.hpp"
 #include "trace.hpp"
@@ -38,6 +40,31 @@ void blocked_scores_kernel(BlockedArgs a, int q0, int nq_blk, int tile0, int n_t
             const int q_local = qb * 32 + tile_row(v, h);
             if (q_local < nq_blk) a.dists[(int64_t)q_local * a.ld + (int64_t)(t - tile0) * 32 + c] = acc[v];
         }
+    }
+}
+
+// Negative control: the same score block with every product rounded to fp16 and the sum kept
+// in fp16 (k ascending, separate multiply and add), one thread per (query, candidate).
+template <int DP>
+__global__ __launch_bounds__(256) void blocked_scores_half_kernel(BlockedArgs a, int q0, int nq_blk, int tile0, int n_tiles,
+                                                                  int d) {
+    const int64_t width = (int64_t)n_tiles * 32;
+    const int64_t total = (int64_t)nq_blk * width;
+    for (int64_t item = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; item < total; item += (int64_t)gridDim.x * blockDim.x) {
+        const int q_local = (int)(item / width);
+        const int64_t j_local = item % width;
+        const int slot = q0 + q_local;
+        int64_t row = a.q_idx ? a.q_idx[slot] : slot;
+        row = min(max(row, (int64_t)0), (int64_t)a.src_rows - 1);
+        const _Float16* qa = reinterpret_cast<const _Float16*>(a.src + row * (DP * 2));
+        const _Float16* cb = reinterpret_cast<const _Float16*>(a.tgt + ((int64_t)tile0 * 32 + j_local) * (DP * 2));
+        _Float16 acc = (_Float16)0.0f;
+        for (int k = 0; k < d; ++k) {
+#pragma clang fp contract(off)
+            const _Float16 p = qa[k] * cb[k];  // rounded to binary16 here: no contraction in this scope
+            acc = acc + p;
+        }
+        a.dists[(int64_t)q_local * a.ld + j_local] = (float)acc;
     }
 }
 
@@ -79,7 +106,7 @@ __global__ __launch_bounds__(256) void blocked_select_kernel(BlockedArgs a, int 
 }
 
 template <int CT, int DP>
-static hipError_t run_blocked_t(const BlockedArgs& a, int block_rows, int block_cols, hipStream_t s) {
+static hipError_t run_blocked_t(const BlockedArgs& a, int d, int block_rows, int block_cols, hipStream_t s) {
     const int m_tiles = (a.m + 31) / 32;
     const int col_tiles = block_cols > 0 ? (block_cols + 31) / 32 : m_tiles;  // 0: the whole of B at once
     for (int q0 = 0; q0 < a.nq; q0 += block_rows) {                           // loop over blocks of A
@@ -88,7 +115,11 @@ static hipError_t run_blocked_t(const BlockedArgs& a, int block_rows, int block_
             const int n_tiles = m_tiles - t0 < col_tiles ? m_tiles - t0 : col_tiles;
             const int64_t units = (int64_t)((nq_blk + 31) / 32) * n_tiles;
             int wgs = (int)((units + 3) / 4 < 8192 ? (units + 3) / 4 : 8192);
-            hipError_t e = launch(TK_BLOCKED, blocked_scores_kernel<CT, DP>, dim3(wgs), dim3(256), 0, s, a, q0, nq_blk, t0, n_tiles);
+            hipError_t e;
+            if (CT == CT_F16 && a.half_accumulate)
+                e = launch(TK_BLOCKED, blocked_scores_half_kernel<DP>, dim3(8192), dim3(256), 0, s, a, q0, nq_blk, t0, n_tiles, d);
+            else
+                e = launch(TK_BLOCKED, blocked_scores_kernel<CT, DP>, dim3(wgs), dim3(256), 0, s, a, q0, nq_blk, t0, n_tiles);
             if (e != hipSuccess) return e;
             wgs = (nq_blk + 3) / 4;
             e = launch(TK_BLOCKED, blocked_select_kernel, dim3(wgs), dim3(256), 0, s, a, q0, nq_blk, t0 * 32, n_tiles * 32,
@@ -99,21 +130,21 @@ static hipError_t run_blocked_t(const BlockedArgs& a, int block_rows, int block_
     return hipSuccess;
 }
 
-hipError_t run_blocked(const BlockedArgs& a, int compute, int dp, int block_rows, int block_cols, hipStream_t s) {
+hipError_t run_blocked(const BlockedArgs& a, int compute, int d, int dp, int block_rows, int block_cols, hipStream_t s) {
     if (a.nq <= 0 || a.m <= 0) return hipSuccess;
     if (compute == FNN_F16) {
-        if (dp == 16) return run_blocked_t<CT_F16, 16>(a, block_rows, block_cols, s);
-        if (dp == 24) return run_blocked_t<CT_F16, 24>(a, block_rows, block_cols, s);
-        if (dp == 32) return run_blocked_t<CT_F16, 32>(a, block_rows, block_cols, s);
+        if (dp == 16) return run_blocked_t<CT_F16, 16>(a, d, block_rows, block_cols, s);
+        if (dp == 24) return run_blocked_t<CT_F16, 24>(a, d, block_rows, block_cols, s);
+        if (dp == 32) return run_blocked_t<CT_F16, 32>(a, d, block_rows, block_cols, s);
     } else if (compute == FNN_BF16) {
-        if (dp == 16) return run_blocked_t<CT_BF16, 16>(a, block_rows, block_cols, s);
-        if (dp == 24) return run_blocked_t<CT_BF16, 24>(a, block_rows, block_cols, s);
-        if (dp == 32) return run_blocked_t<CT_BF16, 32>(a, block_rows, block_cols, s);
+        if (dp == 16) return run_blocked_t<CT_BF16, 16>(a, d, block_rows, block_cols, s);
+        if (dp == 24) return run_blocked_t<CT_BF16, 24>(a, d, block_rows, block_cols, s);
+        if (dp == 32) return run_blocked_t<CT_BF16, 32>(a, d, block_rows, block_cols, s);
     } else {
-        if (dp == 8) return run_blocked_t<CT_F32, 8>(a, block_rows, block_cols, s);
-        if (dp == 16) return run_blocked_t<CT_F32, 16>(a, block_rows, block_cols, s);
-        if (dp == 24) return run_blocked_t<CT_F32, 24>(a, block_rows, block_cols, s);
-        if (dp == 32) return run_blocked_t<CT_F32, 32>(a, block_rows, block_cols, s);
+        if (dp == 8) return run_blocked_t<CT_F32, 8>(a, d, block_rows, block_cols, s);
+        if (dp == 16) return run_blocked_t<CT_F32, 16>(a, d, block_rows, block_cols, s);
+        if (dp == 24) return run_blocked_t<CT_F32, 24>(a, d, block_rows, block_cols, s);
+        if (dp == 32) return run_blocked_t<CT_F32, 32>(a, d, block_rows, block_cols, s);
     }
     return hipErrorInvalidValue;
 }

@@ -90,9 +90,10 @@ struct BlockedArgs {
     int64_t ld;             // columns of the score block (multiple of 32)
     int32_t* out_idx;       // [nq]
     float* out_score;       // [nq] (required: it holds the running best between blocks)
+    int32_t half_accumulate;  // FNN_FLAG_HALF_ACCUMULATE: fp16 products and fp16 sums on the vector ALU
 };
 // block_cols == 0: Algorithm 2 (whole B per block of A); otherwise Algorithm 1 (double loop).
-hipError_t run_blocked(const BlockedArgs& a, int compute, int dp, int block_rows, int block_cols, hipStream_t s);
+hipError_t run_blocked(const BlockedArgs& a, int compute, int d, int dp, int block_rows, int block_cols, hipStream_t s);
 
 // ---- reciprocal iteration bookkeeping ----------------------------------------------------
 struct RecipState {

@@ -101,7 +101,8 @@ def test_argument_errors_are_caught_on_the_host(lib):
     assert _nearest(lib, ok_map, ok_map, _opts(compute=5)) == 3
     assert _nearest(lib, ok_map, ok_map, _opts(max_iter=-1)) == 4      # FNN_E_RANGE
     assert _nearest(lib, ok_map, ok_map, _opts(reserved0=1)) == 4
-    assert _nearest(lib, ok_map, ok_map, _opts(flags=2)) == 4          # unknown flag
+    assert _nearest(lib, ok_map, ok_map, _opts(flags=4)) == 4          # unknown flag
+    assert _nearest(lib, ok_map, ok_map, _opts(flags=2)) == 7          # FNN_E_UNSUPPORTED: fp16 accumulation is blocked-only
     assert _nearest(lib, ok_map, ok_map, opts, ws=0) == 5              # FNN_E_WORKSPACE
     assert _nearest(lib, ok_map, ok_map, opts, ws=0x10001) == 5        # misaligned
     assert _nearest(lib, ok_map, ok_map, opts, ws_bytes=16) == 5       # too small

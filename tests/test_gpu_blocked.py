@@ -34,3 +34,23 @@ def test_query_list_and_agreement_with_the_fused_search():
         check_nearest_gaussian(a[q], b, "f16", host(gi), host(gs), f"blocked {rows}x{cols}")
         assert np.array_equal(host(gi), host(fused_i)[0])          # same arithmetic, other schedule
         assert np.array_equal(host(gs), host(fused_s)[0])
+
+
+def test_half_accumulate_control_matches_its_oracle():
+    # bit-exact: IEEE binary16 multiply and add on both sides
+    a, b = unit_maps(9, 300, 5000, 24)
+    for rows, cols in ((128, 0), (128, 1024)):
+        gi, gs = fnn.fnn_nearest_blocked(dev(a), dev(b), rows, cols, compute="f16", half_accumulate=True)
+        torch.cuda.synchronize()
+        ri, rb = oracle.nearest_half_accumulate(a, b)
+        assert np.array_equal(host(gi), ri)
+        assert np.array_equal(host(gs), rb)
+    a2 = np.array([[32.0, 1.0, 1.0]], dtype=np.float32)
+    b2 = np.array([[64.0, 1.0, 1.0], [64.0, 1.5, 0.0]], dtype=np.float32)
+    gi, gs = fnn.fnn_nearest_blocked(dev(a2), dev(b2), 1, 0, compute="f16", half_accumulate=True)
+    assert host(gi).tolist() == [1] and host(gs).tolist() == [2050.0]
+    gi, gs = fnn.fnn_nearest_blocked(dev(a2), dev(b2), 1, 0, compute="f16")
+    assert host(gi).tolist() == [0] and host(gs).tolist() == [2050.0]
+    # only the blocked entry point offers it, and only for fp16
+    with pytest.raises(fnn.FnnError):
+        fnn.fnn_nearest_blocked(dev(a), dev(b), 128, 0, compute="bf16", half_accumulate=True)

@@ -383,3 +383,25 @@ def test_normalize_closed_forms_and_invariants():
     # the sign pattern and the ordering of channels survive
     assert np.array_equal(np.sign(yz), np.sign(z))
     assert np.array_equal(np.argmax(np.abs(yz), axis=1), np.argmax(np.abs(z), axis=1))
+
+
+# ----------------------------------------------------------- fp16-accumulation control
+def test_half_accumulate_equals_fp32_when_everything_is_exact():
+    # entries k/8, |sum| <= 24: every partial sum is a multiple of 1/64 below 32, exact in fp16
+    a, b = synth.exact_pair(3, 24, 20, 24)
+    idx, best = oracle.nearest_half_accumulate(a, b)
+    ridx, rbest, _ = oracle.nearest(a, b)
+    assert np.array_equal(idx, ridx) and np.array_equal(best, rbest)
+
+
+def test_half_accumulate_worked_flip():
+    # fp16 has steps of 2 between 2048 and 4096.  Query (32, 1, 1):
+    #   candidate 0 = (64, 1, 1): exact 2050; in fp16 2048 + 1 -> 2048 (tie to even), + 1 -> 2048
+    #   candidate 1 = (64, 1.5, 0): exact 2049.5; in fp16 2048 + 1.5 = 2049.5 -> 2050, + 0 -> 2050
+    # so fp32 accumulation prefers candidate 0 and fp16 accumulation prefers candidate 1
+    a = np.array([[32.0, 1.0, 1.0]], dtype=np.float32)
+    b = np.array([[64.0, 1.0, 1.0], [64.0, 1.5, 0.0]], dtype=np.float32)
+    idx, best = oracle.nearest_half_accumulate(a, b)
+    assert idx.tolist() == [1] and best.tolist() == [2050.0]
+    ridx, rbest, rsecond = oracle.nearest(a, b)
+    assert ridx.tolist() == [0] and rbest.tolist() == [2050.0] and rsecond.tolist() == [2049.5]
