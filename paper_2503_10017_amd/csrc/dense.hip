@@ -104,6 +104,21 @@ __device__ __forceinline__ void dense_sweep(const DenseArgs& a, const typename O
     }
 }
 
+// For registers V..15: the lowest lane of each wave half whose x[v] equals tops[v], handed to
+// the lane of that half that holds register v after transpose_max16 (rows 0 of the halves).
+template <int V>
+__device__ __forceinline__ void locate_first_lanes(const float (&x)[16], const float (&tops)[16], int& first_lane) {
+    if constexpr (V < 16) {
+        const u64 hit = __ballot(x[V] == tops[V]);
+        // bit 31 is forced so that the count is defined (and in range) even for an empty mask
+        const int lane_lo = __builtin_ctz((unsigned)hit | 0x80000000u);
+        const int lane_hi = __builtin_ctz((unsigned)(hit >> 32) | 0x80000000u);
+        first_lane = write_lane<holder_lane(V)>(first_lane, lane_lo);
+        first_lane = write_lane<32 + holder_lane(V)>(first_lane, lane_hi);
+        locate_first_lanes<V + 1>(x, tops, first_lane);
+    }
+}
+
 template <int CT, int DP>
 __global__ __launch_bounds__(DENSE_WAVES * 64) __attribute__((amdgpu_waves_per_eu(2)))
 void dense_kernel(DenseArgs a) {
@@ -115,6 +130,8 @@ void dense_kernel(DenseArgs a) {
     const int lane = threadIdx.x & 63, c = lane & 31, h = lane >> 5;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     u64* lds_col_keys = lds + (size_t)a.sb_per_wg * S * 32 + wave * (J * 32);  // this wave's J*32 candidates
+    float* lds_tops = reinterpret_cast<float*>(lds + (size_t)a.sb_per_wg * S * 32 + DENSE_WAVES * (J * 32)) + wave * 32;
+    const int held = held_register(lane);
     const int b = blockIdx.z;
     const float ninf = -__builtin_inff();
 
@@ -157,28 +174,32 @@ void dense_kernel(DenseArgs a) {
             else
                 dense_sweep<CT, DP, false>(a, cand, cmax, qbase, sbg, tbase, lds_row_keys + sb * S * 32, tbase / J, c, h);
 
-            // best query of each resident candidate inside this super-block: reduce the 32
-            // lanes of each half, note the lowest lane that attains the maximum, and let lane v
-            // of each half file the result of register v (one key, one LDS operation per tile)
+            // best query of each resident candidate inside this super-block: a transposing
+            // reduction leaves the maximum of register v with the lanes that hold v; the 16
+            // maxima of a half go round through the wave's LDS words so that every lane can
+            // test its own value against them; the lowest lane that attains each maximum is
+            // read off the comparison mask and handed to the holding lane, which files the key
+            // (one LDS operation per tile)
 #pragma unroll
             for (int jt = 0; jt < J; ++jt) {
-                float my_top = ninf;
-                int my_lo = 0, my_hi = 0;
+                const float top = transpose_max16(cmax[jt], lane);
+                lds_tops[h * 16 + held] = top;  // the two rows of a half store the same value
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                __builtin_amdgcn_wave_barrier();
+                float tops[16];
 #pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    const float x = cmax[jt][v];
-                    const float top = half_max(x);
-                    const u64 hit = __ballot(x == top);
-                    const int lane_lo = __ffsll((unsigned long long)(hit & 0xFFFFFFFFull)) - 1;
-                    const int lane_hi = __ffsll((unsigned long long)(hit >> 32)) - 1;
-                    if (c == v) {
-                        my_top = top;
-                        my_lo = lane_lo;
-                        my_hi = lane_hi;
-                    }
+                for (int q = 0; q < 4; ++q) {
+                    const float4 t4 = reinterpret_cast<const float4*>(lds_tops + h * 16)[q];
+                    tops[4 * q + 0] = t4.x;
+                    tops[4 * q + 1] = t4.y;
+                    tops[4 * q + 2] = t4.z;
+                    tops[4 * q + 3] = t4.w;
                 }
-                if (c < 16 && my_top != ninf)
-                    atomicMax(&lds_col_keys[jt * 32 + tile_row(c, h)], pack_key(my_top, sbg * 32 + (h ? my_hi : my_lo)));
+                __builtin_amdgcn_wave_barrier();
+                int first_lane = 0;
+                locate_first_lanes<0>(cmax[jt], tops, first_lane);
+                if ((lane & 16) == 0 && top != ninf)
+                    atomicMax(&lds_col_keys[jt * 32 + tile_row(held, h)], pack_key(top, sbg * 32 + first_lane));
             }
         }
 
@@ -219,7 +240,7 @@ void dense_resolve_rows_kernel(DenseArgs a, int32_t* nn12, float* s12) {
         int32_t best_j = -1;
         float best = ninf;
         if (key != 0) {
-            const int tbase = min(key_index(key), (a.m_tiles - 1) / J) * J;
+            const int tbase = max(0, min(key_index(key), (a.m_tiles - 1) / J)) * J;
             const Frag q = O::load(d1 + segment_slot(i) * O::ROW_BYTES, h);
             Frag cand[J];
 #pragma unroll
@@ -274,7 +295,7 @@ void dense_resolve_cols_kernel(DenseArgs a, int32_t* nn21, float* s21) {
         int32_t best_i = -1;
         float best = ninf;
         if (key != 0) {
-            const int64_t run0 = (int64_t)min(key_index(key), a.n_sb * 32 - 1) * S;  // first pixel of the run
+            const int64_t run0 = (int64_t)max(0, min(key_index(key), a.n_sb * 32 - 1)) * S;  // first pixel of the run
             const Frag cand = O::load(d2 + (int64_t)j * O::ROW_BYTES, h);
             Frag q[S / 32];
 #pragma unroll
@@ -381,7 +402,8 @@ static hipError_t launch_dense_t(const DenseArgs& a, int batch, int32_t* nn12, f
                                  hipStream_t s) {
     const int groups = (a.m_tiles + DENSE_TILES_PER_GROUP - 1) / DENSE_TILES_PER_GROUP;
     dim3 grid((groups + a.groups_per_wg - 1) / a.groups_per_wg, (a.n_sb + a.sb_per_wg - 1) / a.sb_per_wg, batch);
-    const size_t lds_bytes = ((size_t)a.sb_per_wg * DENSE_S * 32 + DENSE_WAVES * DENSE_J * 32) * sizeof(u64);
+    const size_t lds_bytes = ((size_t)a.sb_per_wg * DENSE_S * 32 + DENSE_WAVES * DENSE_J * 32) * sizeof(u64) +
+                             DENSE_WAVES * 32 * sizeof(float);  // row keys, column keys, 32 maxima per wave
     hipError_t e = launch(TK_DENSE, dense_kernel<CT, DP>, grid, dim3(DENSE_WAVES * 64), lds_bytes, s, a);
     if (e != hipSuccess) return e;
     const int cap = 8192 / batch > 64 ? 8192 / batch : 64;

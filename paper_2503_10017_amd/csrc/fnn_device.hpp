@@ -160,6 +160,60 @@ __device__ __forceinline__ float cross_half_max(float a, float b) {
     return __builtin_fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
 }
 
+// Transposing maximum over the 32 lanes of each wave half, for 16 registers at once.  A
+// plain butterfly costs 5 steps per register; here every step halves the number of live
+// registers instead: after the step that joins lanes l and l^1 a lane keeps only the
+// registers of one parity, after the next step one register in four, and so on, so the 16
+// registers cost 8+4+2+1 select-and-join steps plus one row exchange.  On return lane l
+// holds max over its half of x[held_register(l)].  The later steps join mirrored lanes
+// (l with l^7, l with l^15), so the selection bits are chosen such that both partners of a
+// step hold the same register: e0 = b0^b2, e1 = b1^b2, e2 = b2^b3, e3 = b3 (b = lane bits).
+__device__ __forceinline__ int held_register(int lane) {
+    const int b0 = lane & 1, b1 = (lane >> 1) & 1, b2 = (lane >> 2) & 1, b3 = (lane >> 3) & 1;
+    return (b0 ^ b2) | ((b1 ^ b2) << 1) | ((b2 ^ b3) << 2) | (b3 << 3);
+}
+// Lane (0..15) of a 16-lane row that ends up holding register v: the inverse of held_register.
+__device__ __forceinline__ constexpr int holder_lane(int v) {
+    const int b3 = (v >> 3) & 1, b2 = ((v >> 2) & 1) ^ b3, b1 = ((v >> 1) & 1) ^ b2, b0 = (v & 1) ^ b2;
+    return b0 | (b1 << 1) | (b2 << 2) | (b3 << 3);
+}
+template <int CTRL>
+__device__ __forceinline__ float dpp_max(float x) { return __builtin_fmaxf(x, dpp_move<CTRL>(x)); }
+__device__ __forceinline__ float transpose_max16(const float (&x)[16], int lane) {
+    const int held = held_register(lane);
+    const bool e0 = held & 1, e1 = held & 2, e2 = held & 4, e3 = held & 8;
+    // both sides of every selection are formed first: a cross-lane move must be executed by
+    // all lanes, so it cannot sit inside the arms of a conditional
+    float y8[8], y4[4], y2[2];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {  // joins l and l ^ 1
+        const float even = dpp_max<0xB1>(x[2 * k]), odd = dpp_max<0xB1>(x[2 * k + 1]);
+        y8[k] = e0 ? odd : even;
+    }
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {  // l and l ^ 2
+        const float even = dpp_max<0x4E>(y8[2 * k]), odd = dpp_max<0x4E>(y8[2 * k + 1]);
+        y4[k] = e1 ? odd : even;
+    }
+#pragma unroll
+    for (int k = 0; k < 2; ++k) {  // l and l ^ 7
+        const float even = dpp_max<0x141>(y4[2 * k]), odd = dpp_max<0x141>(y4[2 * k + 1]);
+        y2[k] = e2 ? odd : even;
+    }
+    const float even = dpp_max<0x140>(y2[0]), odd = dpp_max<0x140>(y2[1]);  // l and l ^ 15
+    const float y1 = e3 ? odd : even;
+    const auto sw = __builtin_amdgcn_permlane16_swap(__float_as_uint(y1), __float_as_uint(y1), false, false);
+    return __builtin_fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));                              // both rows
+}
+
+// Lane LANE of `old` replaced by a wave-uniform value (the other lanes keep theirs).
+template <int LANE>
+__device__ __forceinline__ int write_lane(int old, int uniform_value) {
+    static_assert(LANE >= 0 && LANE < 64, "lane of a 64-wide wave");
+    asm("v_writelane_b32 %0, %1, %2" : "+v"(old) : "s"(uniform_value), "n"(LANE));
+    return old;
+}
+
 // Candidate offset inside a tile of result register v for lane half h.
 __device__ __forceinline__ constexpr int tile_row(int v, int h) { return 8 * (v >> 2) + 4 * h + (v & 3); }
 
