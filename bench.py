@@ -60,6 +60,8 @@ def main() -> int:
     ap.add_argument("--latency", action="store_true", help="also time a single pair (adds search launches)")
     ap.add_argument("--contrast", action="store_true",
                     help="also time the paper's blocked schedules (Algorithms 1 and 2 with a materialised score block)")
+    ap.add_argument("--l2", action="store_true",
+                    help="also time the same batch with the squared-distance dist_func (FNN_FLAG_L2)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 256 MiB device copy (reference dispatch for scaling HBM byte counters)")
     args = ap.parse_args()
@@ -214,6 +216,24 @@ def main() -> int:
         dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
+
+    # ---- optional: the same batch with dist_func = squared distance ------------------------------
+    if args.l2:
+        need = fnn.binding.fnn_workspace_bytes_opts(BATCH, N_PIX, N_PIX, D, n_seeds, fnn.binding._opts(compute, l2=True))
+        lws = torch.empty(need, dtype=torch.uint8, device=dev)
+        lout = fnn.fnn_reciprocal(d1, d2, seeds, MAX_ITER, compute, l2=True, workspace=lws)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            fnn.fnn_reciprocal(d1, d2, seeds, MAX_ITER, compute, out=lout, l2=True, workspace=lws)
+        torch.cuda.synchronize()
+        l2_s = (time.perf_counter() - t0) / args.steps
+        result["l2_variant"] = {
+            "ms_per_step": round(l2_s * 1e3, 4), "pairs_per_s": round(BATCH / l2_s, 2),
+            "matches_per_pair": round(float(lout["n_pairs"].float().mean().item()), 1),
+            "note": "same 16 pairs, score = -|a-b|^2/2 through 4 extra channels (rows of 32 instead of 24 channels)",
+        }
+        del lws
 
     # ---- optional: single-pair latency (configs[1]) ----------------------------------------------
     if args.latency:

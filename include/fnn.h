@@ -94,6 +94,21 @@ typedef struct {
  * selection stays in fp32.  Exists to measure how many nearest neighbours that changes.
  */
 #define FNN_FLAG_HALF_ACCUMULATE 2
+/*
+ * FNN_FLAG_L2 (fnn_nearest, fnn_reciprocal, fnn_mutual_dense): dist_func of Algorithms 1-3 is
+ * the squared Euclidean distance instead of the negated dot product -- the choice that
+ * matters for maps that are NOT unit-norm.  score(a, b) = -1/2 * ||a - b||^2 over the
+ * descriptors as rounded to the compute format (so "largest score, lowest index on ties"
+ * is "smallest distance, lowest index on ties"); out_score / s12 / s21 hold that value,
+ * ||a - b||^2 = -2 * score.  It is evaluated on the matrix cores as
+ *   <a, b> - 1/2 ||a||^2 - 1/2 ||b||^2
+ * with the two norm terms carried in spare channels of the prepared rows (each split into
+ * two 16-bit halves for the 16-bit formats), fp32 accumulation.  ||x||^2 is the fp32 sum
+ * (k ascending, squares and sums rounded separately) of the rounded channels.  Needs
+ * d <= 28 (16-bit compute formats) or d <= 30 (FNN_F32), else FNN_E_SHAPE; size the
+ * workspace with fnn_workspace_bytes_opts.  May be combined with FNN_FLAG_NORMALIZE.
+ */
+#define FNN_FLAG_L2 4
 
 typedef struct {
     int32_t compute;      /* fnn_dtype the products are formed in (see above) */
@@ -111,6 +126,12 @@ const char* fnn_status_string(int32_t status);
  * Returns 0 when the shape is invalid.
  */
 size_t fnn_workspace_bytes(int32_t batch, int64_t n, int64_t m, int32_t d, int64_t n_queries, int32_t compute);
+/*
+ * The same for a call that will be made with `opts` (FNN_FLAG_L2 widens the prepared rows);
+ * fnn_workspace_bytes is this function with no flag set.  Returns 0 for invalid shapes or options.
+ */
+size_t fnn_workspace_bytes_opts(int32_t batch, int64_t n, int64_t m, int32_t d, int64_t n_queries,
+                                const fnn_opts* opts);
 
 /*
  * One-directional search (Algorithms 1-3).  For b < batch and q < nq:

@@ -13,6 +13,8 @@ What each function follows:
                        (i, j) is kept when j is i's best candidate and i is j's.
 * ``normalize``     -- the producer step in front of the search: the matching head's maps
                        (section 3.1.4) L2-normalised per pixel, in fp32.
+* ``nearest_l2``    -- the same search with dist_func = squared Euclidean distance (the other
+                       reading of the undefined dist_func; differs on maps that are not unit-norm).
 * ``nearest_half_accumulate`` -- the "naive FP16 only" negative control of section 3.4.4.
 * ``reciprocal``    -- the FastNN iteration (section 3.2, "FastNN Algorithm", steps 1-4),
                        step by step: U^0 = seeds, V^0 = NN_2(U^0); each iteration
@@ -53,6 +55,8 @@ def _load():
             ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32,
             ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
         ]
+        lib.oracle_nearest_l2.restype = None
+        lib.oracle_nearest_l2.argtypes = lib.oracle_nearest.argtypes
         lib.oracle_normalize.restype = None
         lib.oracle_normalize.argtypes = [ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32, ctypes.c_void_p]
         lib.oracle_threads.restype = ctypes.c_int32
@@ -106,6 +110,35 @@ def nearest(a: np.ndarray, b: np.ndarray):
     return idx, best, second
 
 
+def nearest_l2(a: np.ndarray, b: np.ndarray):
+    """For every row of ``a``: lowest index of the row of ``b`` at the smallest squared Euclidean distance.
+
+    Returns (idx int32[K], best float32[K], second float32[K]): the smallest and second smallest
+    squared distance; ``second - best`` is the gap (0 on a tie).
+    """
+    a = np.ascontiguousarray(a, dtype=np.float32)
+    b = np.ascontiguousarray(b, dtype=np.float32)
+    assert a.ndim == 2 and b.ndim == 2 and a.shape[1] == b.shape[1]
+    k, d = a.shape
+    m = b.shape[0]
+    idx = np.empty(k, dtype=np.int32)
+    best = np.empty(k, dtype=np.float32)
+    second = np.empty(k, dtype=np.float32)
+    _load().oracle_nearest_l2(a.ctypes.data, k, b.ctypes.data, m, d,
+                              idx.ctypes.data, best.ctypes.data, second.ctypes.data)
+    return idx, best, second
+
+
+def _search(a, b, metric):
+    """(idx, best, second) with "larger is better" scores: the dot product, or minus the squared distance."""
+    if metric == "dot":
+        return nearest(a, b)
+    if metric == "l2":
+        idx, best, second = nearest_l2(a, b)
+        return idx, -best, -second
+    raise ValueError(f"unknown metric {metric!r}")
+
+
 def nearest_half_accumulate(a: np.ndarray, b: np.ndarray):
     """The "naive FP16 only" control of the paper's HybridCast section (3.4.4): inputs rounded to
     fp16, every product rounded to fp16, the sum accumulated in fp16 (k ascending, multiply and
@@ -125,15 +158,16 @@ def nearest_half_accumulate(a: np.ndarray, b: np.ndarray):
     return idx, scores[np.arange(scores.shape[0]), idx]
 
 
-def mutual_dense(d1: np.ndarray, d2: np.ndarray):
-    """All-pairs mutual nearest neighbours.
+def mutual_dense(d1: np.ndarray, d2: np.ndarray, metric: str = "dot"):
+    """All-pairs mutual nearest neighbours (``metric`` "dot": scores are dot products; "l2": scores
+    are minus the squared distance).
 
     Returns a dict with nn12/s12/gap12 (best candidate in d2 for every row of d1),
     nn21/s21/gap21 (the other direction) and ``pairs`` int32[P][2], the (i, nn12[i]) with
     nn21[nn12[i]] == i, ascending in i.
     """
-    nn12, s12, r12 = nearest(d1, d2)
-    nn21, s21, r21 = nearest(d2, d1)
+    nn12, s12, r12 = _search(d1, d2, metric)
+    nn21, s21, r21 = _search(d2, d1, metric)
     i = np.arange(d1.shape[0], dtype=np.int32)
     keep = (nn12 >= 0)
     keep[keep] = nn21[nn12[keep]] == i[keep]
@@ -145,8 +179,8 @@ def mutual_dense(d1: np.ndarray, d2: np.ndarray):
     }
 
 
-def reciprocal(d1: np.ndarray, d2: np.ndarray, seeds: np.ndarray, max_iter: int):
-    """The FastNN iteration from the given seed pixels of image 1.
+def reciprocal(d1: np.ndarray, d2: np.ndarray, seeds: np.ndarray, max_iter: int, metric: str = "dot"):
+    """The FastNN iteration from the given seed pixels of image 1 (``metric`` as in ``mutual_dense``).
 
     Returns a dict:
       seed_i, seed_j, seed_iter  int32[n_seeds]  per seed: the pair it converged to and the
@@ -171,14 +205,14 @@ def reciprocal(d1: np.ndarray, d2: np.ndarray, seeds: np.ndarray, max_iter: int)
     act = np.arange(n)
     if n:
         # step 1: V^0 = NN_2(U^0)
-        v[act], best, second = nearest(d1[u[act]], d2)
+        v[act], best, second = _search(d1[u[act]], d2, metric)
         min_gap[act] = np.minimum(min_gap[act], best - second)
         searches.append(int(act.size))
     for t in range(max_iter):
         if act.size == 0:
             break
         # step 2: U^{t+1} = NN_1(V^t)
-        u_next, best, second = nearest(d2[v[act]], d1)
+        u_next, best, second = _search(d2[v[act]], d1, metric)
         min_gap[act] = np.minimum(min_gap[act], best - second)
         searches.append(int(act.size))
         conv = u_next == u[act]
@@ -189,7 +223,7 @@ def reciprocal(d1: np.ndarray, d2: np.ndarray, seeds: np.ndarray, max_iter: int)
         if act.size == 0 or t == max_iter - 1:
             break
         u[act] = u_next
-        v[act], best, second = nearest(d1[u[act]], d2)   # V^{t+1} = NN_2(U^{t+1})
+        v[act], best, second = _search(d1[u[act]], d2, metric)   # V^{t+1} = NN_2(U^{t+1})
         min_gap[act] = np.minimum(min_gap[act], best - second)
         searches.append(int(act.size))
 

@@ -56,6 +56,45 @@ void oracle_nearest(const float* a, int64_t k_rows, const float* b, int64_t m_ro
 }
 
 /*
+ * The same search with dist_func = squared Euclidean distance (the other natural reading of
+ * the undefined dist_func of Algorithms 1-3; it ranks differently from the dot product when
+ * the descriptors are not unit-norm).  dist = sum_k (a[k]-b[k])^2 in fp32, k ascending,
+ * every difference, square and sum rounded on its own; "dist < min_dist" as printed, so the
+ * lowest index wins ties.
+ *
+ * best / second: the smallest and second smallest distance (+inf when absent).
+ */
+void oracle_nearest_l2(const float* a, int64_t k_rows, const float* b, int64_t m_rows, int32_t d,
+                       int32_t* idx, float* best, float* second)
+{
+#pragma omp parallel for schedule(dynamic, 16)
+    for (int64_t q = 0; q < k_rows; ++q) {
+        const float* aq = a + q * (int64_t)d;
+        float low = INFINITY, runner_up = INFINITY;
+        int32_t low_j = -1;
+        for (int64_t j = 0; j < m_rows; ++j) {
+            const float* bj = b + j * (int64_t)d;
+            float dist = 0.0f;
+            for (int32_t k = 0; k < d; ++k) {
+                float diff = aq[k] - bj[k];
+                float sq = diff * diff;
+                dist = dist + sq;
+            }
+            if (dist < low) {
+                runner_up = low;
+                low = dist;
+                low_j = (int32_t)j;
+            } else if (dist < runner_up) {
+                runner_up = dist;
+            }
+        }
+        idx[q] = low_j;
+        best[q] = low;
+        second[q] = runner_up;
+    }
+}
+
+/*
  * The producer step in front of the search (paper section 3.1.4, "Matching Head": the maps
  * D1, D2 come out of the head un-normalised): every descriptor divided by its Euclidean norm.
  * norm2 = sum_k x[k]*x[k] in fp32, k ascending, every product and every sum rounded on its

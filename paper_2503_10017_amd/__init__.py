@@ -4,6 +4,7 @@ The work is done by hand-written HIP kernels behind the C ABI in ``include/fnn.h
 (``lib/libfnn.so``); this package only marshals torch tensors into that ABI.  There is
 no CPU or eager fallback: calls raise if the library is missing.
 """
+from . import binding  # noqa: F401
 from .binding import (  # noqa: F401
     FNN_BF16,
     FNN_F16,
@@ -17,6 +18,7 @@ from .binding import (  # noqa: F401
     fnn_trace_begin,
     fnn_trace_end,
     fnn_workspace_bytes,
+    fnn_workspace_bytes_opts,
     library_path,
     load_library,
 )

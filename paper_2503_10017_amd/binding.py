@@ -55,6 +55,8 @@ def load_library():
     lib.fnn_status_string.argtypes = [i32]
     lib.fnn_workspace_bytes.restype = sz
     lib.fnn_workspace_bytes.argtypes = [i32, i64, i64, i32, i64, i32]
+    lib.fnn_workspace_bytes_opts.restype = sz
+    lib.fnn_workspace_bytes_opts.argtypes = [i32, i64, i64, i32, i64, vp]
     lib.fnn_nearest.restype = i32
     lib.fnn_nearest.argtypes = [i32, vp, vp, i64, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.fnn_reciprocal.restype = i32
@@ -116,13 +118,15 @@ def _map_array(views):
 
 FNN_FLAG_NORMALIZE = 1
 FNN_FLAG_HALF_ACCUMULATE = 2
+FNN_FLAG_L2 = 4
 
 
-def _opts(compute, max_iter=0, normalize=False, half_accumulate=False):
+def _opts(compute, max_iter=0, normalize=False, half_accumulate=False, l2=False):
     o = _Opts()
     o.compute = _COMPUTE[compute]
     o.max_iter = int(max_iter)
-    o.flags = (FNN_FLAG_NORMALIZE if normalize else 0) | (FNN_FLAG_HALF_ACCUMULATE if half_accumulate else 0)
+    o.flags = ((FNN_FLAG_NORMALIZE if normalize else 0) | (FNN_FLAG_HALF_ACCUMULATE if half_accumulate else 0) |
+               (FNN_FLAG_L2 if l2 else 0))
     return o
 
 
@@ -140,6 +144,10 @@ def fnn_workspace_bytes(batch: int, n: int, m: int, d: int, n_queries: int, comp
     return int(load_library().fnn_workspace_bytes(batch, n, m, d, n_queries, _COMPUTE[compute]))
 
 
+def fnn_workspace_bytes_opts(batch: int, n: int, m: int, d: int, n_queries: int, opts: "_Opts") -> int:
+    return int(load_library().fnn_workspace_bytes_opts(batch, n, m, d, n_queries, ctypes.byref(opts)))
+
+
 def _workspace(workspace, need, device):
     if workspace is None:
         workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=device)
@@ -149,9 +157,10 @@ def _workspace(workspace, need, device):
 def fnn_nearest(src: MapsLike, tgt: MapsLike, q_idx: Optional[torch.Tensor] = None,
                 nq: Optional[int] = None, nq_active: Optional[torch.Tensor] = None, compute="f16",
                 out_idx: Optional[torch.Tensor] = None, out_score: Optional[torch.Tensor] = None,
-                want_score: bool = True, normalize: bool = False, workspace: Optional[torch.Tensor] = None,
-                stream=None):
-    """One-directional search; returns (out_idx int32[batch][nq], out_score float32[batch][nq] or None)."""
+                want_score: bool = True, normalize: bool = False, l2: bool = False,
+                workspace: Optional[torch.Tensor] = None, stream=None):
+    """One-directional search; returns (out_idx int32[batch][nq], out_score float32[batch][nq] or None).
+    ``l2`` sets FNN_FLAG_L2 (scores are then -1/2 of the squared distance)."""
     lib = load_library()
     sv, tv = _as_pairs(src), _as_pairs(tgt)
     batch = len(sv)
@@ -162,9 +171,9 @@ def fnn_nearest(src: MapsLike, tgt: MapsLike, q_idx: Optional[torch.Tensor] = No
         out_idx = torch.empty((batch, nq), dtype=torch.int32, device=device)
     if out_score is None and want_score:
         out_score = torch.empty((batch, nq), dtype=torch.float32, device=device)
-    need = fnn_workspace_bytes(batch, sv[0].shape[0], tv[0].shape[0], sv[0].shape[1], nq, compute)
+    o = _opts(compute, normalize=normalize, l2=l2)
+    need = fnn_workspace_bytes_opts(batch, sv[0].shape[0], tv[0].shape[0], sv[0].shape[1], nq, o)
     workspace = _workspace(workspace, need, device)
-    o = _opts(compute, normalize=normalize)
     sa, ta = _map_array(sv), _map_array(tv)
     st = lib.fnn_nearest(batch, ctypes.cast(sa, ctypes.c_void_p), _ptr(q_idx), nq, _ptr(nq_active),
                          ctypes.cast(ta, ctypes.c_void_p), ctypes.byref(o), _ptr(out_idx), _ptr(out_score),
@@ -175,8 +184,8 @@ def fnn_nearest(src: MapsLike, tgt: MapsLike, q_idx: Optional[torch.Tensor] = No
 
 
 def fnn_reciprocal(d1: MapsLike, d2: MapsLike, seeds: torch.Tensor, max_iter: int = 10, compute="f16",
-                   out: Optional[dict] = None, normalize: bool = False, workspace: Optional[torch.Tensor] = None,
-                   stream=None):
+                   out: Optional[dict] = None, normalize: bool = False, l2: bool = False,
+                   workspace: Optional[torch.Tensor] = None, stream=None):
     """The FastNN iteration; returns a dict of device tensors
     seed_i, seed_j, seed_iter [batch][n_seeds], pairs [batch][n_seeds][2], n_pairs [batch]."""
     lib = load_library()
@@ -192,9 +201,9 @@ def fnn_reciprocal(d1: MapsLike, d2: MapsLike, seeds: torch.Tensor, max_iter: in
             "pairs": torch.empty((batch, n_seeds, 2), dtype=torch.int32, device=device),
             "n_pairs": torch.empty((batch,), dtype=torch.int32, device=device),
         }
-    need = fnn_workspace_bytes(batch, v1[0].shape[0], v2[0].shape[0], v1[0].shape[1], n_seeds, compute)
+    o = _opts(compute, max_iter, normalize, l2=l2)
+    need = fnn_workspace_bytes_opts(batch, v1[0].shape[0], v2[0].shape[0], v1[0].shape[1], n_seeds, o)
     workspace = _workspace(workspace, need, device)
-    o = _opts(compute, max_iter, normalize)
     a1, a2 = _map_array(v1), _map_array(v2)
     st = lib.fnn_reciprocal(batch, ctypes.cast(a1, ctypes.c_void_p), ctypes.cast(a2, ctypes.c_void_p),
                             _ptr(seeds), n_seeds, ctypes.byref(o),
@@ -207,7 +216,8 @@ def fnn_reciprocal(d1: MapsLike, d2: MapsLike, seeds: torch.Tensor, max_iter: in
 
 
 def fnn_mutual_dense(d1: MapsLike, d2: MapsLike, compute="f16", out: Optional[dict] = None,
-                     normalize: bool = False, workspace: Optional[torch.Tensor] = None, stream=None):
+                     normalize: bool = False, l2: bool = False, workspace: Optional[torch.Tensor] = None,
+                     stream=None):
     """All-pairs mutual nearest neighbours; returns a dict of device tensors
     nn12, s12 [batch][n], nn21, s21 [batch][m], pairs [batch][min(n,m)][2], n_pairs [batch]."""
     lib = load_library()
@@ -224,9 +234,9 @@ def fnn_mutual_dense(d1: MapsLike, d2: MapsLike, compute="f16", out: Optional[di
             "pairs": torch.empty((batch, min(n, m), 2), dtype=torch.int32, device=device),
             "n_pairs": torch.empty((batch,), dtype=torch.int32, device=device),
         }
-    need = fnn_workspace_bytes(batch, n, m, v1[0].shape[1], 0, compute)
+    o = _opts(compute, normalize=normalize, l2=l2)
+    need = fnn_workspace_bytes_opts(batch, n, m, v1[0].shape[1], 0, o)
     workspace = _workspace(workspace, need, device)
-    o = _opts(compute, normalize=normalize)
     a1, a2 = _map_array(v1), _map_array(v2)
     st = lib.fnn_mutual_dense(batch, ctypes.cast(a1, ctypes.c_void_p), ctypes.cast(a2, ctypes.c_void_p),
                               ctypes.byref(o), _ptr(out["nn12"]), _ptr(out.get("s12")), _ptr(out["nn21"]),

@@ -123,10 +123,17 @@ int32_t check_opts(const fnn_opts* o) {
     if (!o) return FNN_E_NULL;
     if (!valid_dtype(o->compute)) return FNN_E_DTYPE;
     if (o->max_iter < 0) return FNN_E_RANGE;
-    if (o->flags & ~(FNN_FLAG_NORMALIZE | FNN_FLAG_HALF_ACCUMULATE)) return FNN_E_RANGE;
+    if (o->flags & ~(FNN_FLAG_NORMALIZE | FNN_FLAG_HALF_ACCUMULATE | FNN_FLAG_L2)) return FNN_E_RANGE;
     for (int i = 0; i < 5; ++i)
         if (o->reserved[i] != 0) return FNN_E_RANGE;
     return FNN_OK;
+}
+
+// Channels the prepared rows must hold for this call (descriptor + L2 norm channels), or
+// -1 when they do not fit the widest row the kernels take.
+int32_t row_channels(int32_t d, const fnn_opts* o) {
+    const int32_t de = effective_d(d, o->compute, (o->flags & FNN_FLAG_L2) != 0);
+    return de <= FNN_MAX_D ? de : -1;
 }
 
 int32_t check_workspace(const void* ws, size_t have, size_t need) {
@@ -135,8 +142,9 @@ int32_t check_workspace(const void* ws, size_t have, size_t need) {
     return FNN_OK;
 }
 
-void fill_prep_side(PrepSide& sd, int32_t batch, const fnn_map* maps, int64_t n_pad, void* dst) {
+void fill_prep_side(PrepSide& sd, int32_t batch, const fnn_map* maps, int64_t n_pad, void* dst, int second_image) {
     memset(&sd, 0, sizeof(sd));
+    sd.second_image = second_image;
     for (int b = 0; b < batch; ++b) sd.src[b] = maps[b].data;
     sd.n = maps[0].n;
     sd.n_pad = n_pad;
@@ -151,15 +159,16 @@ hipError_t prep_both(int32_t batch, const fnn_map* a, const fnn_map* b, const Ma
     PrepArgs pa;
     memset(&pa, 0, sizeof(pa));
     pa.extra = extra;
-    fill_prep_side(pa.side[0], batch, a, L.n_pad, L.p1);
+    fill_prep_side(pa.side[0], batch, a, L.n_pad, L.p1, 0);
     pa.side[0].segment_major = first_segment_major ? 1 : 0;
-    fill_prep_side(pa.side[1], batch, b, L.m_pad, L.p2);
+    fill_prep_side(pa.side[1], batch, b, L.m_pad, L.p2, 1);
     pa.n_sides = 2;
     pa.batch = batch;
     pa.d = d;
     pa.dp = L.dp;
     pa.compute = compute;
     pa.normalize = (opts->flags & FNN_FLAG_NORMALIZE) ? 1 : 0;
+    pa.l2 = (opts->flags & FNN_FLAG_L2) ? 1 : 0;
     return launch_prep(pa, s);
 }
 
@@ -187,25 +196,36 @@ const char* fnn_status_string(int32_t status) {
     }
 }
 
-size_t fnn_workspace_bytes(int32_t batch, int64_t n, int64_t m, int32_t d, int64_t n_queries, int32_t compute) {
-    if (!shape_ok(batch, n, m, d, n_queries) || !valid_dtype(compute)) return 0;
+size_t fnn_workspace_bytes_opts(int32_t batch, int64_t n, int64_t m, int32_t d, int64_t n_queries,
+                                const fnn_opts* opts) {
+    if (!shape_ok(batch, n, m, d, n_queries) || check_opts(opts) != FNN_OK) return 0;
+    const int32_t de = row_channels(d, opts);
+    if (de < 0) return 0;
+    const int32_t compute = opts->compute;
     size_t most = 0;
     {
         Carver cv{nullptr, 0};
-        carve_nearest(cv, batch, n, m, d, n_queries, compute);
+        carve_nearest(cv, batch, n, m, de, n_queries, compute);
         most = cv.used;
     }
     {
         Carver cv{nullptr, 0};
-        carve_recip(cv, batch, n, m, d, n_queries, compute);
+        carve_recip(cv, batch, n, m, de, n_queries, compute);
         if (cv.used > most) most = cv.used;
     }
     {
         Carver cv{nullptr, 0};
-        carve_dense(cv, batch, n, m, d, compute);
+        carve_dense(cv, batch, n, m, de, compute);
         if (cv.used > most) most = cv.used;
     }
     return most + WS_ALIGN;
+}
+
+size_t fnn_workspace_bytes(int32_t batch, int64_t n, int64_t m, int32_t d, int64_t n_queries, int32_t compute) {
+    fnn_opts o;
+    memset(&o, 0, sizeof(o));
+    o.compute = compute;
+    return fnn_workspace_bytes_opts(batch, n, m, d, n_queries, &o);
 }
 
 int32_t fnn_nearest(int32_t batch, const fnn_map* src, const int32_t* q_idx, int64_t nq, const int32_t* nq_active,
@@ -222,13 +242,15 @@ int32_t fnn_nearest(int32_t batch, const fnn_map* src, const int32_t* q_idx, int
     const int64_t n = src[0].n, m = tgt[0].n;
     const int32_t d = src[0].d;
     if (tgt[0].d != d || nq < 0 || nq > MAX_PIXELS) return FNN_E_SHAPE;
+    const int32_t de = row_channels(d, opts);
+    if (de < 0) return FNN_E_SHAPE;
     if (!q_idx && nq > n) return FNN_E_SHAPE;
     if (nq > 0 && n == 0) return FNN_E_SHAPE;
     if (nq > 0 && !out_idx) return FNN_E_NULL;
     if (nq == 0) return FNN_OK;
 
     Carver cv{(char*)workspace, 0};
-    NearestLayout L = carve_nearest(cv, batch, n, m, d, nq, opts->compute);
+    NearestLayout L = carve_nearest(cv, batch, n, m, de, nq, opts->compute);
     st = check_workspace(workspace, workspace_bytes, cv.used);
     if (st != FNN_OK) return st;
     hipStream_t s = (hipStream_t)stream;
@@ -276,6 +298,7 @@ int32_t fnn_nearest_blocked(const fnn_map* src, const int32_t* q_idx, int64_t nq
     st = check_opts(opts);
     if (st != FNN_OK) return st;
     if ((opts->flags & FNN_FLAG_HALF_ACCUMULATE) && opts->compute != FNN_F16) return FNN_E_UNSUPPORTED;
+    if (opts->flags & FNN_FLAG_L2) return FNN_E_UNSUPPORTED;
     const int64_t n = src[0].n, m = tgt[0].n;
     const int32_t d = src[0].d;
     if (tgt[0].d != d || nq < 0 || nq > MAX_PIXELS || block_rows < 1 || block_cols < 0) return FNN_E_SHAPE;
@@ -329,12 +352,14 @@ int32_t fnn_reciprocal(int32_t batch, const fnn_map* d1, const fnn_map* d2, cons
     const int64_t n = d1[0].n, m = d2[0].n;
     const int32_t d = d1[0].d;
     if (d2[0].d != d || n_seeds < 0 || n_seeds > MAX_PIXELS) return FNN_E_SHAPE;
+    const int32_t de = row_channels(d, opts);
+    if (de < 0) return FNN_E_SHAPE;
     if (n_seeds > 0 && (n == 0 || m == 0)) return FNN_E_SHAPE;
     if (!n_pairs) return FNN_E_NULL;
     if (n_seeds > 0 && (!seeds || !seed_i || !seed_j || !seed_iter || !pairs)) return FNN_E_NULL;
 
     Carver cv{(char*)workspace, 0};
-    RecipLayout L = carve_recip(cv, batch, n, m, d, n_seeds, opts->compute);
+    RecipLayout L = carve_recip(cv, batch, n, m, de, n_seeds, opts->compute);
     st = check_workspace(workspace, workspace_bytes, cv.used);
     if (st != FNN_OK) return st;
     hipStream_t s = (hipStream_t)stream;
@@ -424,12 +449,14 @@ int32_t fnn_mutual_dense(int32_t batch, const fnn_map* d1, const fnn_map* d2, co
     const int64_t n = d1[0].n, m = d2[0].n;
     const int32_t d = d1[0].d;
     if (d2[0].d != d) return FNN_E_SHAPE;
+    const int32_t de = row_channels(d, opts);
+    if (de < 0) return FNN_E_SHAPE;
     if (!n_pairs) return FNN_E_NULL;
     if ((n > 0 && !nn12) || (m > 0 && !nn21)) return FNN_E_NULL;
     if (n > 0 && m > 0 && !pairs) return FNN_E_NULL;
 
     Carver cv{(char*)workspace, 0};
-    DenseLayout L = carve_dense(cv, batch, n, m, d, opts->compute);
+    DenseLayout L = carve_dense(cv, batch, n, m, de, opts->compute);
     st = check_workspace(workspace, workspace_bytes, cv.used);
     if (st != FNN_OK) return st;
     hipStream_t s = (hipStream_t)stream;

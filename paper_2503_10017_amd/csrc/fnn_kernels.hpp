@@ -17,6 +17,10 @@ inline int padded_d(int d, int compute) {
     if (compute == FNN_F32) return (d + 7) / 8 * 8;
     return d <= 16 ? 16 : (d <= 24 ? 24 : 32);
 }
+// Channels of a prepared row that carry data: the descriptor plus, for the L2 score, the
+// norm terms and their unit partners (two 16-bit halves each, or one fp32 value each).
+inline int l2_extra_channels(int compute) { return compute == FNN_F32 ? 2 : 4; }
+inline int effective_d(int d, int compute, bool l2) { return l2 ? d + l2_extra_channels(compute) : d; }
 inline int elem_size(int dtype) { return dtype == FNN_F32 ? 4 : 2; }
 inline int64_t round_up(int64_t x, int64_t a) { return (x + a - 1) / a * a; }
 
@@ -28,6 +32,7 @@ struct PrepSide {
     int32_t segment_major;           // 1: rows are stored in the dense kernel's segment-major order
     int64_t row_stride;              // source row stride, elements
     int32_t dtype;                   // source storage format
+    int32_t second_image;            // L2 score: 0 = rows [x, 1.., -|x|^2/2..], 1 = rows [x, -|x|^2/2.., 1..]
     void* dst;                       // [batch][n_pad][dp] in the compute format
 };
 // Small initialisations that ride along with the prepare launch instead of costing launches
@@ -50,6 +55,7 @@ struct PrepArgs {
     int32_t dp;
     int32_t compute;
     int32_t normalize;  // divide every descriptor by its Euclidean norm first (FNN_FLAG_NORMALIZE)
+    int32_t l2;         // append the norm channels of the L2 score (FNN_FLAG_L2)
 };
 hipError_t launch_prep(const PrepArgs& a, hipStream_t s);
 hipError_t launch_fill_u64(u64* p, int64_t count, u64 value, hipStream_t s);

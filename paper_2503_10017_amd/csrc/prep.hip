@@ -40,6 +40,27 @@ __device__ __forceinline__ float descriptor_norm(const void* src, int64_t first,
     return __fsqrt_rn(sum);
 }
 
+// x as the compute format holds it (round to nearest even), back in fp32.
+__device__ __forceinline__ float round_to_compute(float x, int compute) {
+    if (compute == FNN_F16) return (float)(_Float16)x;
+    if (compute == FNN_BF16) return __uint_as_float((uint32_t)float_to_bf16_rne(x) << 16);
+    return x;
+}
+
+// -1/2 * |x|^2 of one descriptor AS PREPARED (normalised if asked, rounded to the compute
+// format): fp32 sum, channels ascending, squares and sums rounded separately.
+__device__ __forceinline__ float minus_half_norm2(const void* src, int64_t first, int d, int dtype, int compute,
+                                                  float divide_by) {
+    float sum = 0.0f;
+    for (int k = 0; k < d; ++k) {
+        float x = load_as_float(src, first + k, dtype);
+        if (divide_by > 0.0f) x = __fdiv_rn(x, divide_by);
+        x = round_to_compute(x, compute);
+        sum = __fadd_rn(sum, __fmul_rn(x, x));
+    }
+    return -0.5f * sum;
+}
+
 // Side jobs spread over all threads of the launch (see PrepExtra).
 __device__ __forceinline__ void prep_side_jobs(const PrepArgs& a) {
     const PrepExtra& x = a.extra;
@@ -79,11 +100,29 @@ __global__ __launch_bounds__(256) void prep_kernel(PrepArgs a) {
             const int k = g * 8 + e;
             v[e] = (pix < sd.n && k < a.d) ? load_as_float(src, pix * sd.row_stride + k, sd.dtype) : 0.0f;
         }
+        float norm = 0.0f;
         if (a.normalize && pix < sd.n) {
-            const float norm = descriptor_norm(src, pix * sd.row_stride, a.d, sd.dtype);
+            norm = descriptor_norm(src, pix * sd.row_stride, a.d, sd.dtype);
             if (norm > 0.0f) {
 #pragma unroll
                 for (int e = 0; e < 8; ++e) v[e] = __fdiv_rn(v[e], norm);
+            }
+        }
+        // L2 score: channels d.. hold the unit partners and -|x|^2/2 (see FNN_FLAG_L2).  For a
+        // 16-bit format the norm term is split into a rounded value and the rounded remainder.
+        const int extra = a.compute == FNN_F32 ? 1 : 2;
+        if (a.l2 && pix < sd.n && g * 8 + 8 > a.d && g * 8 < a.d + 2 * extra) {
+            const float term = minus_half_norm2(src, pix * sd.row_stride, a.d, sd.dtype, a.compute, norm);
+            const float hi = round_to_compute(term, a.compute);
+            const float lo = round_to_compute(term - hi, a.compute);
+            const int ones0 = a.d + (sd.second_image ? extra : 0);   // first unit channel
+            const int term0 = a.d + (sd.second_image ? 0 : extra);   // first norm channel
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const int k = g * 8 + e;
+                if (k >= ones0 && k < ones0 + extra) v[e] = 1.0f;
+                if (k == term0) v[e] = hi;
+                if (extra == 2 && k == term0 + 1) v[e] = lo;
             }
         }
         if (a.compute == FNN_F32) {
@@ -191,7 +230,7 @@ hipError_t launch_prep(const PrepArgs& a, hipStream_t s) {
     int64_t blocks = (most + 255) / 256;
     if (blocks > 4096) blocks = 4096;
     dim3 grid((unsigned)blocks, (unsigned)(a.n_sides * a.batch));
-    bool fast = a.d == a.dp && most < (int64_t)1 << 31;
+    bool fast = a.d == a.dp && !a.l2 && most < (int64_t)1 << 31;
     for (int i = 0; i < a.n_sides && fast; ++i) {
         const PrepSide& sd = a.side[i];
         fast = sd.dtype == FNN_F32 && sd.row_stride % 4 == 0;

@@ -31,7 +31,7 @@ def test_every_declared_symbol_is_exported(lib):
     names = declared_functions()
     assert names == ["fnn_blocked_workspace_bytes", "fnn_mutual_dense", "fnn_nearest", "fnn_nearest_blocked",
                      "fnn_reciprocal", "fnn_status_string", "fnn_trace_begin", "fnn_trace_end", "fnn_trace_kind_name",
-                     "fnn_workspace_bytes"]
+                     "fnn_workspace_bytes", "fnn_workspace_bytes_opts"]
     for name in names:
         assert hasattr(lib, name), name
 
@@ -54,6 +54,12 @@ def test_workspace_bytes(lib):
     assert fnn.fnn_workspace_bytes(1, 10, 10, 33, 1, "f16") == 0     # d out of range
     assert fnn.fnn_workspace_bytes(1, -1, 10, 24, 1, "f16") == 0
     assert fnn.fnn_workspace_bytes(65, 10, 10, 24, 1, "f16") == 0
+    # the options-aware query: no flag = the plain one; squared distance widens 24-channel rows to 32
+    plain, wide = binding._opts("f16"), binding._opts("f16", l2=True)
+    assert binding.fnn_workspace_bytes_opts(1, 196608, 196608, 24, 3072, plain) == big
+    assert binding.fnn_workspace_bytes_opts(1, 196608, 196608, 24, 3072, wide) >= big + 2 * 196608 * 8 * 2
+    assert binding.fnn_workspace_bytes_opts(1, 64, 64, 29, 8, wide) == 0            # 29 + 4 channels do not fit
+    assert binding.fnn_workspace_bytes_opts(1, 64, 64, 12, 8, wide) == binding.fnn_workspace_bytes_opts(1, 64, 64, 16, 8, plain)
 
 
 def _map(n=64, d=24, dtype=0, stride=None, data=0x1000):
@@ -101,8 +107,11 @@ def test_argument_errors_are_caught_on_the_host(lib):
     assert _nearest(lib, ok_map, ok_map, _opts(compute=5)) == 3
     assert _nearest(lib, ok_map, ok_map, _opts(max_iter=-1)) == 4      # FNN_E_RANGE
     assert _nearest(lib, ok_map, ok_map, _opts(reserved0=1)) == 4
-    assert _nearest(lib, ok_map, ok_map, _opts(flags=4)) == 4          # unknown flag
+    assert _nearest(lib, ok_map, ok_map, _opts(flags=8)) == 4          # unknown flag
     assert _nearest(lib, ok_map, ok_map, _opts(flags=2)) == 7          # FNN_E_UNSUPPORTED: fp16 accumulation is blocked-only
+    assert _nearest(lib, _map(d=29), _map(d=29), _opts(flags=4)) == 2  # squared distance: 29 + 4 channels do not fit
+    assert _nearest(lib, _map(d=31), _map(d=31), _opts(compute=0, flags=4)) == 2
+    assert _nearest(lib, ok_map, ok_map, _opts(flags=6)) == 7          # fp16 accumulation wins: unsupported here
     assert _nearest(lib, ok_map, ok_map, opts, ws=0) == 5              # FNN_E_WORKSPACE
     assert _nearest(lib, ok_map, ok_map, opts, ws=0x10001) == 5        # misaligned
     assert _nearest(lib, ok_map, ok_map, opts, ws_bytes=16) == 5       # too small

@@ -405,3 +405,104 @@ def test_half_accumulate_worked_flip():
     assert idx.tolist() == [1] and best.tolist() == [2050.0]
     ridx, rbest, rsecond = oracle.nearest(a, b)
     assert ridx.tolist() == [0] and rbest.tolist() == [2050.0] and rsecond.tolist() == [2049.5]
+
+
+# --------------------------------------------------------- squared-distance dist_func: pins
+def test_nearest_l2_matches_kdtree_on_exact_inputs():
+    # scipy's k-d tree is an independent algorithm; on multiples of 1/8 every distance is exact
+    # in fp32 and in float64, so the distances must agree bit for bit and the index wherever the
+    # nearest candidate is unique
+    rng = np.random.default_rng(21)
+    a = rng.integers(-8, 9, size=(211, 6)).astype(np.float32) / 8
+    b = rng.integers(-8, 9, size=(997, 6)).astype(np.float32) / 8
+    idx, best, second = oracle.nearest_l2(a, b)
+    dist, tidx = cKDTree(b.astype(np.float64)).query(a.astype(np.float64), k=2)
+    # the tree reports distances, the oracle their squares: both exact, so the correctly rounded
+    # float64 square roots must coincide
+    assert np.array_equal(np.sqrt(best.astype(np.float64)), dist[:, 0])
+    assert np.array_equal(np.sqrt(second.astype(np.float64)), dist[:, 1])
+    unique = second > best
+    assert unique.sum() > 50 and (~unique).sum() > 5
+    assert np.array_equal(idx[unique], tidx[unique, 0])
+    # among equals the lowest index: no earlier candidate is as close
+    for q in np.nonzero(~unique)[0]:
+        d2 = ((b.astype(np.float64) - a[q].astype(np.float64)) ** 2).sum(axis=1)
+        assert idx[q] == int(np.nonzero(d2 == d2.min())[0][0])
+
+
+def test_nearest_l2_on_unit_vectors_is_the_dot_product_search():
+    # |a - b|^2 = 2 - 2<a, b> for unit vectors: same neighbours, distances from the scores
+    rng = np.random.default_rng(22)
+    a, b = unit_rows(rng, 300, 24), unit_rows(rng, 2000, 24)
+    li, lbest, lsecond = oracle.nearest_l2(a, b)
+    di, dbest, dsecond = oracle.nearest(a, b)
+    clear = (dbest - dsecond) > 1e-5
+    assert clear.mean() > 0.95
+    assert np.array_equal(li[clear], di[clear])
+    assert np.allclose(lbest, 2.0 - 2.0 * dbest, atol=2e-6)
+
+
+def test_nearest_l2_differs_from_the_dot_product_where_it_must():
+    # worked by hand: the query is the origin, so every dot product is 0 (tie -> index 0), while
+    # the distances are 9, 4, 4, 16 -> index 1 (the first of the two at distance 4)
+    a = np.zeros((1, 2), dtype=np.float32)
+    b = np.array([[3, 0], [0, 2], [2, 0], [0, -4]], dtype=np.float32)
+    assert oracle.nearest(a, b)[0].tolist() == [0]
+    idx, best, second = oracle.nearest_l2(a, b)
+    assert idx.tolist() == [1] and best.tolist() == [4.0] and second.tolist() == [4.0]
+    # a long candidate wins the dot product but not the distance
+    a = np.array([[1, 0]], dtype=np.float32)
+    b = np.array([[1, 0.5], [8, 0]], dtype=np.float32)
+    assert oracle.nearest(a, b)[0].tolist() == [1]
+    idx, best, second = oracle.nearest_l2(a, b)
+    assert idx.tolist() == [0] and best.tolist() == [0.25] and second.tolist() == [49.0]
+
+
+def test_nearest_l2_is_translation_invariant_and_symmetric_in_value():
+    rng = np.random.default_rng(23)
+    a = rng.integers(-8, 9, size=(64, 5)).astype(np.float32) / 8
+    b = rng.integers(-8, 9, size=(200, 5)).astype(np.float32) / 8
+    shift = rng.integers(-8, 9, size=(1, 5)).astype(np.float32) / 4
+    i0, b0, s0 = oracle.nearest_l2(a, b)
+    i1, b1, s1 = oracle.nearest_l2(a + shift, b + shift)          # still exact: small dyadic numbers
+    assert np.array_equal(i0, i1) and np.array_equal(b0, b1) and np.array_equal(s0, s1)
+    # d(a, b) = d(b, a): the distance of a's neighbour is what b's search sees for that pair
+    j0, c0, _ = oracle.nearest_l2(b, a)
+    for q in range(a.shape[0]):
+        assert c0[i0[q]] <= b0[q]                                  # b's own best is at least as close
+    # empty candidate set
+    idx, best, second = oracle.nearest_l2(a, np.zeros((0, 5), dtype=np.float32))
+    assert (idx == -1).all() and np.isinf(best).all() and np.isinf(second).all()
+
+
+def test_l2_matching_on_unit_maps_equals_dot_matching():
+    # the whole iteration and the dense filter only see the ranking, which is the same
+    d1, d2 = synth.warped_pair(31, 24, 16, 8)[:2]
+    seeds = synth.grid_seeds(24, 16, 4)
+    rd = oracle.reciprocal(d1, d2, seeds, 10, metric="dot")
+    rl = oracle.reciprocal(d1, d2, seeds, 10, metric="l2")
+    clear = rd["min_gap"] > 1e-5
+    assert clear.mean() > 0.9
+    for key in ("seed_i", "seed_j", "seed_iter"):
+        assert np.array_equal(rd[key][clear], rl[key][clear])
+    md, ml = oracle.mutual_dense(d1, d2), oracle.mutual_dense(d1, d2, metric="l2")
+    ok = (md["gap12"] > 1e-5)
+    assert np.array_equal(md["nn12"][ok], ml["nn12"][ok])
+    assert np.allclose(ml["s12"], -(2.0 - 2.0 * md["s12"]), atol=2e-6)
+
+
+def test_l2_reciprocal_invariants_on_raw_maps():
+    # un-normalised maps: pairs are mutually nearest in distance and a fixed point of one more step
+    rng = np.random.default_rng(32)
+    d1 = rng.standard_normal((24 * 16, 8)).astype(np.float32)
+    d2 = (d1[rng.permutation(d1.shape[0])] + 0.1 * rng.standard_normal(d1.shape)).astype(np.float32)
+    seeds = synth.grid_seeds(24, 16, 2)
+    r = oracle.reciprocal(d1, d2, seeds, 10, metric="l2")
+    dense = oracle.mutual_dense(d1, d2, metric="l2")
+    dense_pairs = {tuple(p) for p in dense["pairs"].tolist()}
+    assert len(r["pairs"]) > 10
+    for i, j in r["pairs"].tolist():
+        assert (i, j) in dense_pairs
+        assert oracle.nearest_l2(d1[i:i + 1], d2)[0][0] == j and oracle.nearest_l2(d2[j:j + 1], d1)[0][0] == i
+    # and it is not the dot-product answer: the maps are far from unit norm
+    assert not np.array_equal(dense["nn12"], oracle.mutual_dense(d1, d2)["nn12"])
