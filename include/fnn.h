@@ -184,6 +184,27 @@ int32_t fnn_mutual_dense(int32_t batch, const fnn_map* d1, const fnn_map* d2, co
                          void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * The match set in the problem statement's own terms (section 3.1, "Problem Statement": a
+ * correspondence is a pair of pixels i = (w_i, h_i), j = (w_j, h_j)), optionally thinned by
+ * the confidence maps c1, c2 that the regression heads emit (section 3.1.3).  For pair b and
+ * p < min(n_pairs[b], max_pairs), in input order, the match (i, j) = pairs[b][p] is KEPT iff
+ *   0 <= i < n, 0 <= j < m,
+ *   conf1 == NULL or conf1[b*n + i] >= min_conf1,  conf2 == NULL or conf2[b*m + j] >= min_conf2
+ * (the paper names the confidence maps but prints no rule; this threshold test is this
+ * library's reading; a NaN confidence drops the match), and kept matches are written
+ * densely, order preserved, as
+ *   out_xy[b][q] = (i mod width1, i div width1, j mod width2, j div width2);
+ * rows q >= out_count[b] are set to -1.  `pairs` / `n_pairs` are the outputs of
+ * fnn_reciprocal or fnn_mutual_dense (device memory, max_pairs rows per pair); the two
+ * images may differ in size.  No workspace.  out_xy must not alias pairs.
+ * Errors: FNN_E_NULL, FNN_E_SHAPE (batch, widths < 1, negative sizes).
+ */
+int32_t fnn_pairs_to_pixels(int32_t batch, const int32_t* pairs, const int32_t* n_pairs, int64_t max_pairs,
+                            int64_t n, int32_t width1, int64_t m, int32_t width2, const float* conf1,
+                            const float* conf2, float min_conf1, float min_conf2, int32_t* out_xy,
+                            int32_t* out_count, void* stream);
+
+/*
  * The paper's own search schedules, for comparison with fnn_nearest (same results, one image
  * pair): block_cols == 0 runs Algorithm 2 ("FastNN-Lite", section 3.4.3): a single loop over
  * blocks of block_rows queries, each scored against the WHOLE candidate map into a

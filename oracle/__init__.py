@@ -15,6 +15,8 @@ What each function follows:
                        (section 3.1.4) L2-normalised per pixel, in fp32.
 * ``nearest_l2``    -- the same search with dist_func = squared Euclidean distance (the other
                        reading of the undefined dist_func; differs on maps that are not unit-norm).
+* ``pairs_to_pixels`` -- the step after the path: matches as (w, h) pixel coordinates (section 3.1),
+                       thinned by the confidence maps of section 3.1.3.
 * ``nearest_half_accumulate`` -- the "naive FP16 only" negative control of section 3.4.4.
 * ``reciprocal``    -- the FastNN iteration (section 3.2, "FastNN Algorithm", steps 1-4),
                        step by step: U^0 = seeds, V^0 = NN_2(U^0); each iteration
@@ -156,6 +158,23 @@ def nearest_half_accumulate(a: np.ndarray, b: np.ndarray):
     scores = acc.astype(np.float32)
     idx = np.argmax(scores, axis=1).astype(np.int32)              # first maximum = lowest index
     return idx, scores[np.arange(scores.shape[0]), idx]
+
+
+def pairs_to_pixels(pairs: np.ndarray, width1: int, width2: int, n: int, m: int, conf1=None, conf2=None,
+                    min_conf1: float = 0.0, min_conf2: float = 0.0) -> np.ndarray:
+    """The matches (flat pixel ids) as the paper's problem statement writes them (section 3.1):
+    i = (w_i, h_i), j = (w_j, h_j), keeping only matches whose confidences (section 3.1.3's maps
+    c1, c2, when given) reach the thresholds.  One match at a time, in order; int32[P'][4]."""
+    rows = []
+    for i, j in np.asarray(pairs).reshape(-1, 2).tolist():
+        if not (0 <= i < n and 0 <= j < m):
+            continue
+        if conf1 is not None and not (np.float32(conf1[i]) >= np.float32(min_conf1)):
+            continue
+        if conf2 is not None and not (np.float32(conf2[j]) >= np.float32(min_conf2)):
+            continue
+        rows.append((i % width1, i // width1, j % width2, j // width2))
+    return np.asarray(rows, dtype=np.int32).reshape(-1, 4)
 
 
 def mutual_dense(d1: np.ndarray, d2: np.ndarray, metric: str = "dot"):

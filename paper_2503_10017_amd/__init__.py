@@ -13,6 +13,7 @@ from .binding import (  # noqa: F401
     fnn_mutual_dense,
     fnn_nearest,
     fnn_nearest_blocked,
+    fnn_pairs_to_pixels,
     fnn_reciprocal,
     fnn_status_string,
     fnn_trace_begin,

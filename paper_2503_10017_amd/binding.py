@@ -67,6 +67,9 @@ def load_library():
     lib.fnn_blocked_workspace_bytes.argtypes = [i64, i64, i32, i32, i32, i32]
     lib.fnn_nearest_blocked.restype = i32
     lib.fnn_nearest_blocked.argtypes = [vp, vp, i64, vp, vp, i32, i32, vp, vp, vp, sz, vp]
+    lib.fnn_pairs_to_pixels.restype = i32
+    lib.fnn_pairs_to_pixels.argtypes = [i32, vp, vp, i64, i64, i32, i64, i32, vp, vp, ctypes.c_float, ctypes.c_float,
+                                        vp, vp, vp]
     lib.fnn_trace_begin.restype = i32
     lib.fnn_trace_begin.argtypes = [i32]
     lib.fnn_trace_end.restype = i32
@@ -268,6 +271,24 @@ def fnn_nearest_blocked(src: torch.Tensor, tgt: torch.Tensor, block_rows: int, b
     if st != 0:
         raise FnnError(st, "fnn_nearest_blocked")
     return out_idx, out_score
+
+
+def fnn_pairs_to_pixels(pairs: torch.Tensor, n_pairs: torch.Tensor, n: int, width1: int, m: int, width2: int,
+                        conf1: Optional[torch.Tensor] = None, conf2: Optional[torch.Tensor] = None,
+                        min_conf1: float = 0.0, min_conf2: float = 0.0, stream=None):
+    """Matches as pixel coordinates with an optional confidence filter; ``pairs`` int32[batch][max_pairs][2].
+    Returns (out_xy int32[batch][max_pairs][4], out_count int32[batch])."""
+    lib = load_library()
+    batch, max_pairs = pairs.shape[0], pairs.shape[1]
+    device = pairs.device
+    out_xy = torch.empty((batch, max_pairs, 4), dtype=torch.int32, device=device)
+    out_count = torch.empty((batch,), dtype=torch.int32, device=device)
+    st = lib.fnn_pairs_to_pixels(batch, _ptr(pairs), _ptr(n_pairs), max_pairs, n, width1, m, width2, _ptr(conf1),
+                                 _ptr(conf2), float(min_conf1), float(min_conf2), _ptr(out_xy), _ptr(out_count),
+                                 _stream_ptr(stream, device))
+    if st != 0:
+        raise FnnError(st, "fnn_pairs_to_pixels")
+    return out_xy, out_count
 
 
 def fnn_trace_begin(max_kernels: int = 4096) -> None:

@@ -512,5 +512,32 @@ int32_t fnn_mutual_dense(int32_t batch, const fnn_map* d1, const fnn_map* d2, co
     return FNN_OK;
 }
 
+int32_t fnn_pairs_to_pixels(int32_t batch, const int32_t* pairs, const int32_t* n_pairs, int64_t max_pairs, int64_t n,
+                            int32_t width1, int64_t m, int32_t width2, const float* conf1, const float* conf2,
+                            float min_conf1, float min_conf2, int32_t* out_xy, int32_t* out_count, void* stream) {
+    if (batch < 1 || batch > FNN_MAX_BATCH || max_pairs < 0 || max_pairs > MAX_PIXELS || n < 0 || m < 0 ||
+        n > MAX_PIXELS || m > MAX_PIXELS || width1 < 1 || width2 < 1)
+        return FNN_E_SHAPE;
+    if (!n_pairs || !out_count) return FNN_E_NULL;
+    if (max_pairs > 0 && (!pairs || !out_xy)) return FNN_E_NULL;
+    PixelArgs pa;
+    memset(&pa, 0, sizeof(pa));
+    pa.pairs = pairs;
+    pa.n_pairs = n_pairs;
+    pa.max_pairs = max_pairs;
+    pa.n = n;
+    pa.m = m;
+    pa.width1 = width1;
+    pa.width2 = width2;
+    pa.conf1 = conf1;
+    pa.conf2 = conf2;
+    pa.min_conf1 = min_conf1;
+    pa.min_conf2 = min_conf2;
+    pa.out_xy = out_xy;
+    pa.out_count = out_count;
+    FNN_TRY(launch_pairs_to_pixels(pa, batch, (hipStream_t)stream));
+    return FNN_OK;
+}
+
 }  // extern "C"
 #pragma GCC visibility pop

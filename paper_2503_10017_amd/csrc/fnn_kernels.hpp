@@ -152,4 +152,19 @@ struct DenseFinalArgs {
 };
 hipError_t launch_dense_final(const DenseFinalArgs& a, int batch, hipStream_t s);
 
+// ---- matches as pixel coordinates, confidence filter -------------------------------------
+struct PixelArgs {
+    const int32_t* pairs;    // [batch][max_pairs][2] flat pixel ids (i in image 1, j in image 2)
+    const int32_t* n_pairs;  // [batch]
+    int64_t max_pairs;
+    int64_t n, m;            // pixels per image
+    int32_t width1, width2;
+    const float* conf1;      // [batch][n] or NULL
+    const float* conf2;      // [batch][m] or NULL
+    float min_conf1, min_conf2;
+    int32_t* out_xy;         // [batch][max_pairs][4]
+    int32_t* out_count;      // [batch]
+};
+hipError_t launch_pairs_to_pixels(const PixelArgs& a, int batch, hipStream_t s);
+
 }  // namespace fnn

@@ -91,6 +91,7 @@ const char* fnn_trace_kind_name(int32_t kind) {
         case TK_RESOLVE: return "resolve_kernel";
         case TK_DENSE_RESOLVE: return "dense_resolve_kernels";
         case TK_BLOCKED: return "blocked_kernels";
+        case TK_PIXELS: return "pairs_to_pixels_kernel";
         default: return "unknown";
     }
 }

@@ -20,7 +20,8 @@ enum TraceKind : int {
     TK_RESOLVE = 9,
     TK_DENSE_RESOLVE = 10,
     TK_BLOCKED = 11,
-    TK_COUNT = 12
+    TK_PIXELS = 12,
+    TK_COUNT = 13
 };
 
 // Returns false when no trace is open or it is full; otherwise hands out the next event pair.

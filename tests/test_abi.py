@@ -30,7 +30,7 @@ def declared_functions():
 def test_every_declared_symbol_is_exported(lib):
     names = declared_functions()
     assert names == ["fnn_blocked_workspace_bytes", "fnn_mutual_dense", "fnn_nearest", "fnn_nearest_blocked",
-                     "fnn_reciprocal", "fnn_status_string", "fnn_trace_begin", "fnn_trace_end", "fnn_trace_kind_name",
+                     "fnn_pairs_to_pixels", "fnn_reciprocal", "fnn_status_string", "fnn_trace_begin", "fnn_trace_end", "fnn_trace_kind_name",
                      "fnn_workspace_bytes", "fnn_workspace_bytes_opts"]
     for name in names:
         assert hasattr(lib, name), name
@@ -158,3 +158,16 @@ def test_binding_fails_loudly_without_the_library(monkeypatch, tmp_path):
     monkeypatch.setattr(binding, "_LIB_PATH", str(tmp_path / "nope" / "libfnn.so"))
     with pytest.raises(RuntimeError, match="no fallback"):
         binding.load_library()
+
+
+def test_pairs_to_pixels_argument_errors(lib):
+    vp, f = ctypes.c_void_p, ctypes.c_float
+
+    def call(batch=1, pairs=0x1000, n_pairs=0x2000, max_pairs=16, n=64, w1=8, m=64, w2=8, out=0x3000, count=0x4000):
+        return lib.fnn_pairs_to_pixels(batch, vp(pairs) if pairs else None, vp(n_pairs) if n_pairs else None, max_pairs,
+                                       n, w1, m, w2, None, None, f(0.0), f(0.0), vp(out) if out else None,
+                                       vp(count) if count else None, None)
+
+    assert call(batch=0) == 2 and call(batch=65) == 2
+    assert call(w1=0) == 2 and call(w2=-3) == 2 and call(max_pairs=-1) == 2 and call(n=-1) == 2
+    assert call(n_pairs=0) == 1 and call(count=0) == 1 and call(pairs=0) == 1 and call(out=0) == 1

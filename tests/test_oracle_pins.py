@@ -506,3 +506,37 @@ def test_l2_reciprocal_invariants_on_raw_maps():
         assert oracle.nearest_l2(d1[i:i + 1], d2)[0][0] == j and oracle.nearest_l2(d2[j:j + 1], d1)[0][0] == i
     # and it is not the dot-product answer: the maps are far from unit norm
     assert not np.array_equal(dense["nn12"], oracle.mutual_dense(d1, d2)["nn12"])
+
+
+# ------------------------------------------------------ matches as pixel coordinates: pins
+def test_pairs_to_pixels_worked_example():
+    # images of width 5 (3 rows) and width 4 (2 rows); worked by hand:
+    #   pixel 7 of image 1 = (w 2, h 1), 14 = (4, 2), 0 = (0, 0); pixel 6 of image 2 = (2, 1), 3 = (3, 0), 7 = (3, 1)
+    pairs = np.array([[0, 3], [7, 6], [14, 7]], dtype=np.int32)
+    xy = oracle.pairs_to_pixels(pairs, 5, 4, 15, 8)
+    assert xy.tolist() == [[0, 0, 3, 0], [2, 1, 2, 1], [4, 2, 3, 1]]
+    conf1 = np.array([0.9] * 7 + [0.2] + [0.9] * 7, dtype=np.float32)       # pixel 7 is unsure
+    conf2 = np.array([0.5] * 8, dtype=np.float32)
+    assert oracle.pairs_to_pixels(pairs, 5, 4, 15, 8, conf1, conf2, 0.3, 0.5).tolist() == [[0, 0, 3, 0], [4, 2, 3, 1]]
+    assert oracle.pairs_to_pixels(pairs, 5, 4, 15, 8, conf1, conf2, 0.3, 0.6).shape == (0, 4)
+    # ">=": a confidence equal to the threshold stays; NaN never does; ids outside the image are dropped
+    conf2[3] = np.nan
+    assert oracle.pairs_to_pixels(pairs, 5, 4, 15, 8, None, conf2, 0.0, 0.5).tolist() == [[2, 1, 2, 1], [4, 2, 3, 1]]
+    assert oracle.pairs_to_pixels(np.array([[15, 0], [-1, 2], [3, 8]]), 5, 4, 15, 8).shape == (0, 4)
+
+
+def test_pairs_to_pixels_round_trip_and_monotone_filter():
+    rng = np.random.default_rng(41)
+    w1, h1, w2, h2 = 37, 11, 23, 29
+    pairs = np.stack([rng.integers(0, w1 * h1, 500), rng.integers(0, w2 * h2, 500)], axis=1).astype(np.int32)
+    xy = oracle.pairs_to_pixels(pairs, w1, w2, w1 * h1, w2 * h2)
+    assert xy.shape == (500, 4)
+    assert np.array_equal(xy[:, 1] * w1 + xy[:, 0], pairs[:, 0]) and np.array_equal(xy[:, 3] * w2 + xy[:, 2], pairs[:, 1])
+    assert (xy[:, 0] < w1).all() and (xy[:, 1] < h1).all() and (xy[:, 2] < w2).all() and (xy[:, 3] < h2).all()
+    conf1, conf2 = rng.random(w1 * h1).astype(np.float32), rng.random(w2 * h2).astype(np.float32)
+    counts = [oracle.pairs_to_pixels(pairs, w1, w2, w1 * h1, w2 * h2, conf1, conf2, t, t).shape[0] for t in (0.0, 0.3, 0.6, 1.1)]
+    assert counts[0] == 500 and counts[-1] == 0 and counts == sorted(counts, reverse=True)
+    # the survivors are a subsequence of the unfiltered list (order kept)
+    kept = oracle.pairs_to_pixels(pairs, w1, w2, w1 * h1, w2 * h2, conf1, conf2, 0.3, 0.3).tolist()
+    it = iter(xy.tolist())
+    assert all(any(row == other for other in it) for row in kept)
