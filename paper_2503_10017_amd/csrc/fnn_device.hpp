@@ -76,6 +76,17 @@ struct Ops {
         return f;
     }
 
+    // The same for lane c of a 32-pixel tile whose address `tile` is the same in every lane:
+    // written as uniform base + 32-bit lane offset so that the load takes its base from scalar
+    // registers and a streaming loop spends no vector instruction on addresses.
+    static __device__ __forceinline__ Frag load_tile(const char* tile, uint32_t c, int h) {
+        const uint32_t off = c * (uint32_t)ROW_BYTES + (uint32_t)h * (uint32_t)LANE_BYTES;
+        Frag f;
+#pragma unroll
+        for (int i = 0; i < NV; ++i) f.v[i] = *reinterpret_cast<const uint4*>(tile + (off + 16u * i));
+        return f;
+    }
+
     static __device__ __forceinline__ f32x16 mma(const Frag& a, const Frag& b) {
         f32x16 acc = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 #pragma unroll
@@ -114,6 +125,14 @@ struct OpsHalf24 {
         Frag f;
         f.lo = *reinterpret_cast<const uint4*>(row + 16 * h);
         f.hi = *reinterpret_cast<const uint2*>(row + 32 + 8 * h);
+        return f;
+    }
+
+    // uniform tile address + 32-bit lane offsets (see Ops::load_tile)
+    static __device__ __forceinline__ Frag load_tile(const char* tile, uint32_t c, int h) {
+        Frag f;
+        f.lo = *reinterpret_cast<const uint4*>(tile + (c * 48u + 16u * (uint32_t)h));
+        f.hi = *reinterpret_cast<const uint2*>(tile + (c * 48u + 32u + 8u * (uint32_t)h));
         return f;
     }
 

@@ -97,7 +97,7 @@ void search_kernel(SearchArgs a) {
         Frag ring[P];
 #pragma unroll
         for (int p = 0; p < P; ++p)
-            ring[p] = O::load(tgt + ((int64_t)min(t0 + p, t1 - 1) * 32 + c) * O::ROW_BYTES, h);
+            ring[p] = O::load_tile(tgt + (int64_t)min(t0 + p, t1 - 1) * (32 * O::ROW_BYTES), c, h);
 
         // blocks past the live queries of the last row group are computed on row 0 and dropped
         Frag q[R];
@@ -118,7 +118,7 @@ void search_kernel(SearchArgs a) {
                 const int t = tb + p;
                 if (t < t1) {  // uniform
                     const Frag cur = ring[p];
-                    ring[p] = O::load(tgt + ((int64_t)min(t + P, t1 - 1) * 32 + c) * O::ROW_BYTES, h);
+                    ring[p] = O::load_tile(tgt + (int64_t)min(t + P, t1 - 1) * (32 * O::ROW_BYTES), c, h);
                     f32x16 acc[R];
 #pragma unroll
                     for (int r = 0; r < R; ++r) acc[r] = O::mma(cur, q[r]);
