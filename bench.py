@@ -219,7 +219,7 @@ def main() -> int:
 
     # ---- optional: the same batch with dist_func = squared distance ------------------------------
     if args.l2:
-        need = fnn.binding.fnn_workspace_bytes_opts(BATCH, N_PIX, N_PIX, D, n_seeds, fnn.binding._opts(compute, l2=True))
+        need = fnn.fnn_workspace_bytes_opts(BATCH, N_PIX, N_PIX, D, n_seeds, compute, l2=True)
         lws = torch.empty(need, dtype=torch.uint8, device=dev)
         lout = fnn.fnn_reciprocal(d1, d2, seeds, MAX_ITER, compute, l2=True, workspace=lws)
         torch.cuda.synchronize()

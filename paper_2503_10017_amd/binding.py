@@ -147,8 +147,11 @@ def fnn_workspace_bytes(batch: int, n: int, m: int, d: int, n_queries: int, comp
     return int(load_library().fnn_workspace_bytes(batch, n, m, d, n_queries, _COMPUTE[compute]))
 
 
-def fnn_workspace_bytes_opts(batch: int, n: int, m: int, d: int, n_queries: int, opts: "_Opts") -> int:
-    return int(load_library().fnn_workspace_bytes_opts(batch, n, m, d, n_queries, ctypes.byref(opts)))
+def fnn_workspace_bytes_opts(batch: int, n: int, m: int, d: int, n_queries: int, compute, max_iter: int = 0,
+                             normalize: bool = False, l2: bool = False) -> int:
+    """Workspace for a call made with these options (0 when shape or options are invalid)."""
+    o = _opts(compute, max_iter, normalize, l2=l2)
+    return int(load_library().fnn_workspace_bytes_opts(batch, n, m, d, n_queries, ctypes.byref(o)))
 
 
 def _workspace(workspace, need, device):
@@ -175,7 +178,7 @@ def fnn_nearest(src: MapsLike, tgt: MapsLike, q_idx: Optional[torch.Tensor] = No
     if out_score is None and want_score:
         out_score = torch.empty((batch, nq), dtype=torch.float32, device=device)
     o = _opts(compute, normalize=normalize, l2=l2)
-    need = fnn_workspace_bytes_opts(batch, sv[0].shape[0], tv[0].shape[0], sv[0].shape[1], nq, o)
+    need = fnn_workspace_bytes_opts(batch, sv[0].shape[0], tv[0].shape[0], sv[0].shape[1], nq, compute, l2=l2)
     workspace = _workspace(workspace, need, device)
     sa, ta = _map_array(sv), _map_array(tv)
     st = lib.fnn_nearest(batch, ctypes.cast(sa, ctypes.c_void_p), _ptr(q_idx), nq, _ptr(nq_active),
@@ -205,7 +208,7 @@ def fnn_reciprocal(d1: MapsLike, d2: MapsLike, seeds: torch.Tensor, max_iter: in
             "n_pairs": torch.empty((batch,), dtype=torch.int32, device=device),
         }
     o = _opts(compute, max_iter, normalize, l2=l2)
-    need = fnn_workspace_bytes_opts(batch, v1[0].shape[0], v2[0].shape[0], v1[0].shape[1], n_seeds, o)
+    need = fnn_workspace_bytes_opts(batch, v1[0].shape[0], v2[0].shape[0], v1[0].shape[1], n_seeds, compute, l2=l2)
     workspace = _workspace(workspace, need, device)
     a1, a2 = _map_array(v1), _map_array(v2)
     st = lib.fnn_reciprocal(batch, ctypes.cast(a1, ctypes.c_void_p), ctypes.cast(a2, ctypes.c_void_p),
@@ -238,7 +241,7 @@ def fnn_mutual_dense(d1: MapsLike, d2: MapsLike, compute="f16", out: Optional[di
             "n_pairs": torch.empty((batch,), dtype=torch.int32, device=device),
         }
     o = _opts(compute, normalize=normalize, l2=l2)
-    need = fnn_workspace_bytes_opts(batch, n, m, v1[0].shape[1], 0, o)
+    need = fnn_workspace_bytes_opts(batch, n, m, v1[0].shape[1], 0, compute, l2=l2)
     workspace = _workspace(workspace, need, device)
     a1, a2 = _map_array(v1), _map_array(v2)
     st = lib.fnn_mutual_dense(batch, ctypes.cast(a1, ctypes.c_void_p), ctypes.cast(a2, ctypes.c_void_p),

@@ -55,11 +55,11 @@ def test_workspace_bytes(lib):
     assert fnn.fnn_workspace_bytes(1, -1, 10, 24, 1, "f16") == 0
     assert fnn.fnn_workspace_bytes(65, 10, 10, 24, 1, "f16") == 0
     # the options-aware query: no flag = the plain one; squared distance widens 24-channel rows to 32
-    plain, wide = binding._opts("f16"), binding._opts("f16", l2=True)
-    assert binding.fnn_workspace_bytes_opts(1, 196608, 196608, 24, 3072, plain) == big
-    assert binding.fnn_workspace_bytes_opts(1, 196608, 196608, 24, 3072, wide) >= big + 2 * 196608 * 8 * 2
-    assert binding.fnn_workspace_bytes_opts(1, 64, 64, 29, 8, wide) == 0            # 29 + 4 channels do not fit
-    assert binding.fnn_workspace_bytes_opts(1, 64, 64, 12, 8, wide) == binding.fnn_workspace_bytes_opts(1, 64, 64, 16, 8, plain)
+    assert fnn.fnn_workspace_bytes_opts(1, 196608, 196608, 24, 3072, "f16") == big
+    assert fnn.fnn_workspace_bytes_opts(1, 196608, 196608, 24, 3072, "f16", l2=True) >= big + 2 * 196608 * 8 * 2
+    assert fnn.fnn_workspace_bytes_opts(1, 64, 64, 29, 8, "f16", l2=True) == 0      # 29 + 4 channels do not fit
+    assert fnn.fnn_workspace_bytes_opts(1, 64, 64, 12, 8, "f16", l2=True) == fnn.fnn_workspace_bytes_opts(1, 64, 64, 16, 8, "f16")
+    assert fnn.fnn_workspace_bytes_opts(1, 64, 64, 24, 8, "f16", max_iter=-1) == 0  # invalid options
 
 
 def _map(n=64, d=24, dtype=0, stride=None, data=0x1000):
