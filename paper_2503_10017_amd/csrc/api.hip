@@ -85,15 +85,35 @@ struct DenseLayout {
     MapsLayout maps;
     u64* row_keys;
     u64* col_keys;
+    int32_t* unit_counts;
+    int64_t zero_words;  // 64-bit words from row_keys to the end of unit_counts
+    int32_t row_units, col_units;
+    int64_t rows_cap, cols_cap;
+    int32_t* unit_cursor;
+    int32_t* lists;
+    int32_t* chunk_unit;
+    int32_t* chunk_totals;
     int32_t* block_counts;
     int64_t blocks_per_pair;
 };
 DenseLayout carve_dense(Carver& cv, int batch, int64_t n, int64_t m, int d, int compute) {
     DenseLayout L;
     L.maps = carve_maps(cv, batch, n, m, d, compute, 32 * DENSE_S);
-    // the two key tables are adjacent so that one fill clears both
+    // the two key tables and the bucket counters are adjacent so that one range clears them all
+    const size_t z0 = cv.used;
     L.row_keys = (u64*)cv.take((size_t)batch * (n + m) * sizeof(u64));
     L.col_keys = L.row_keys ? L.row_keys + (size_t)batch * n : nullptr;
+    L.row_units = (int32_t)((L.maps.m_pad / 32 + DENSE_J - 1) / DENSE_J);
+    L.col_units = (int32_t)(L.maps.n_pad / DENSE_S);
+    const size_t units = (size_t)batch * ((size_t)L.row_units + L.col_units);
+    L.unit_counts = (int32_t*)cv.take(units * sizeof(int32_t));
+    L.zero_words = (int64_t)((cv.used - z0) / sizeof(u64));
+    L.unit_cursor = (int32_t*)cv.take(units * sizeof(int32_t));
+    L.rows_cap = round_up(n, 32) + 32 * (int64_t)L.row_units;
+    L.cols_cap = round_up(m, 32) + 32 * (int64_t)L.col_units;
+    L.lists = (int32_t*)cv.take((size_t)batch * (L.rows_cap + L.cols_cap) * sizeof(int32_t));
+    L.chunk_unit = (int32_t*)cv.take((size_t)batch * ((L.rows_cap + L.cols_cap) / 32) * sizeof(int32_t));
+    L.chunk_totals = (int32_t*)cv.take((size_t)batch * 2 * sizeof(int32_t));
     const int64_t most = n > m ? n : m;
     L.blocks_per_pair = (most + 1023) / 1024;
     L.block_counts = (int32_t*)cv.take((size_t)batch * (L.blocks_per_pair + 1) * sizeof(int32_t));
@@ -463,8 +483,8 @@ int32_t fnn_mutual_dense(int32_t batch, const fnn_map* d1, const fnn_map* d2, co
 
     PrepExtra extra;
     memset(&extra, 0, sizeof(extra));
-    extra.zero_ptr = L.row_keys;  // both key tables start empty
-    extra.zero_count = (int64_t)batch * (n + m);
+    extra.zero_ptr = L.row_keys;  // both key tables and the bucket counters start empty
+    extra.zero_count = L.zero_words;
     if (n > 0 && m > 0) FNN_TRY(prep_both(batch, d1, d2, L.maps, d, opts, s, extra, true));
 
     DenseArgs da;
@@ -479,6 +499,15 @@ int32_t fnn_mutual_dense(int32_t batch, const fnn_map* d1, const fnn_map* d2, co
     da.m_tiles = (int32_t)(L.maps.m_pad / 32);
     da.row_keys = L.row_keys;
     da.col_keys = L.col_keys;
+    da.row_units = L.row_units;
+    da.col_units = L.col_units;
+    da.rows_cap = L.rows_cap;
+    da.cols_cap = L.cols_cap;
+    da.unit_counts = L.unit_counts;
+    da.unit_cursor = L.unit_cursor;
+    da.lists = L.lists;
+    da.chunk_unit = L.chunk_unit;
+    da.chunk_totals = L.chunk_totals;
     // Workgroup tile: up to 3 query super-blocks (48 KB of LDS keys) x up to 4 candidate
     // groups.  Larger tiles mean fewer merges into the global key tables; small problems
     // shrink the tile until the grid covers the chip a few times.

@@ -17,9 +17,10 @@
 //   Locations are ordered like the pixels they cover, so "largest score, then lowest
 //   location" (a 64-bit max on packed keys) always keeps the run that holds the lowest
 //   index among equal scores.
-// Pass 2 (dense_resolve_*) recomputes, per query and per candidate, just the winning run
-// with the same matrix instruction -- bit-identical scores -- and names the lowest index
-// that attains the maximum.  Then the reciprocity filter and an ordered compaction.
+// Pass 2 buckets the pixels by their winning unit and recomputes, 32 pixels of one unit at a
+// time, just that unit with the same matrix instruction -- bit-identical scores -- and names
+// the lowest index that attains the maximum.  Then the reciprocity filter and an ordered
+// compaction.
 #include "dense_perm.hpp"
 #include "fnn_device.hpp"
 #include "fnn_kernels.hpp"
@@ -220,8 +221,115 @@ void dense_kernel(DenseArgs a) {
     }
 }
 
-// Pass 2, queries: one wave per pixel i of image 1 recomputes the J tiles of the winning
-// group with i replicated into every column and picks the lowest candidate at the maximum.
+// ---- pass 2: exact indices ---------------------------------------------------------------
+// Every query knows the group of J tiles that holds its best candidate, every candidate the
+// run of S queries that holds its best query.  Resolving them one by one would read a whole
+// group (6 KB) or run (3 KB) per pixel and use one column of each matrix product.  Instead
+// the pixels are first bucketed by their winning unit (count, scan, fill: a counting sort
+// whose order inside a bucket does not matter); a wave then takes 32 pixels of ONE unit,
+// reads the unit once and resolves all 32 with full 32x32 products -- the same matrix
+// instruction on the same operands as pass 1, so every score has the bits pass 1 saw.
+// Buckets are padded to whole chunks of 32 with -1.
+constexpr int BUCKET_THREADS = 1024;
+
+__device__ __forceinline__ int row_unit_of(const DenseArgs& a, u64 key) {
+    return max(0, min(key_index(key), a.row_units - 1));
+}
+__device__ __forceinline__ int col_unit_of(const DenseArgs& a, u64 key) {
+    return max(0, min(key_index(key), a.col_units - 1));
+}
+
+__global__ __launch_bounds__(BUCKET_THREADS) void dense_bucket_count_kernel(DenseArgs a) {
+    const int b = blockIdx.y;
+    const int i = blockIdx.x * BUCKET_THREADS + threadIdx.x;
+    int32_t* counts = a.unit_counts + (int64_t)b * (a.row_units + a.col_units);
+    if (i < a.n) {
+        const u64 key = a.row_keys[(int64_t)b * a.n + i];
+        if (key) atomicAdd(&counts[row_unit_of(a, key)], 1);
+    }
+    if (i < a.m) {
+        const u64 key = a.col_keys[(int64_t)b * a.m + i];
+        if (key) atomicAdd(&counts[a.row_units + col_unit_of(a, key)], 1);
+    }
+}
+
+// blockIdx.x = side (0: queries by tile group, 1: candidates by run), blockIdx.y = pair.
+// Exclusive scan of the bucket sizes rounded up to chunks of 32; writes each bucket's first
+// list position (the fill cursor), the unit of every chunk, the -1 padding and the chunk total.
+__global__ __launch_bounds__(BUCKET_THREADS) void dense_bucket_scan_kernel(DenseArgs a) {
+    __shared__ int wave_sums[BUCKET_THREADS / 64];
+    const int side = blockIdx.x, b = blockIdx.y;
+    const int n_units = side ? a.col_units : a.row_units;
+    const int unit0 = side ? a.row_units : 0;
+    const int64_t list0 = side ? a.rows_cap : 0;
+    const int32_t* counts = a.unit_counts + (int64_t)b * (a.row_units + a.col_units) + unit0;
+    int32_t* cursor = a.unit_cursor + (int64_t)b * (a.row_units + a.col_units) + unit0;
+    int32_t* list = a.lists + (int64_t)b * (a.rows_cap + a.cols_cap) + list0;
+    int32_t* chunk_unit = a.chunk_unit + ((int64_t)b * (a.rows_cap + a.cols_cap) + list0) / 32;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    int running = 0;  // chunks before this round of units
+    for (int start = 0; start < n_units; start += BUCKET_THREADS) {
+        const int u = start + (int)threadIdx.x;
+        const int count = u < n_units ? counts[u] : 0;
+        const int chunks = (count + 31) / 32;
+        int x = chunks;
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+            const int y = __shfl_up(x, d);
+            if (lane >= d) x += y;
+        }
+        __syncthreads();
+        if (lane == 63) wave_sums[wave] = x;
+        __syncthreads();
+        int offset = 0, sum = 0;
+        for (int w = 0; w < BUCKET_THREADS / 64; ++w) {
+            if (w < wave) offset += wave_sums[w];
+            sum += wave_sums[w];
+        }
+        const int first = running + offset + x - chunks;  // first chunk of this unit
+        if (u < n_units) {
+            cursor[u] = first * 32;
+            for (int k = 0; k < chunks; ++k) chunk_unit[first + k] = u;
+            for (int p = first * 32 + count; p < (first + chunks) * 32; ++p) list[p] = -1;
+        }
+        running += sum;
+    }
+    if (threadIdx.x == 0) a.chunk_totals[b * 2 + side] = running;
+}
+
+// Every pixel takes the next free position of its bucket.  A pixel without a key (no
+// candidate at all) gets its final "none" result here.
+__global__ __launch_bounds__(BUCKET_THREADS) void dense_bucket_fill_kernel(DenseArgs a, int32_t* nn12, float* s12,
+                                                                           int32_t* nn21, float* s21) {
+    const int b = blockIdx.y;
+    const int i = blockIdx.x * BUCKET_THREADS + threadIdx.x;
+    int32_t* cursor = a.unit_cursor + (int64_t)b * (a.row_units + a.col_units);
+    int32_t* list = a.lists + (int64_t)b * (a.rows_cap + a.cols_cap);
+    if (i < a.n) {
+        const u64 key = a.row_keys[(int64_t)b * a.n + i];
+        if (key) {
+            list[atomicAdd(&cursor[row_unit_of(a, key)], 1)] = i;
+        } else {
+            nn12[(int64_t)b * a.n + i] = -1;
+            if (s12) s12[(int64_t)b * a.n + i] = -__builtin_inff();
+        }
+    }
+    if (i < a.m) {
+        const u64 key = a.col_keys[(int64_t)b * a.m + i];
+        if (key) {
+            list[a.rows_cap + atomicAdd(&cursor[a.row_units + col_unit_of(a, key)], 1)] = i;
+        } else {
+            nn21[(int64_t)b * a.m + i] = -1;
+            if (s21) s21[(int64_t)b * a.m + i] = -__builtin_inff();
+        }
+    }
+}
+
+// Queries: a wave takes 32 queries whose best candidate lies in the same group of J tiles.
+// Lane c holds query list[c]; result register v of lane (c, h) for tile jt is that query's
+// score against candidate (tbase + jt)*32 + tile_row(v, h), so the lowest index at the
+// maximum is found inside the lane (registers ascend with the candidate) and across its
+// two halves.
 template <int CT, int DP>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2)))
 void dense_resolve_rows_kernel(DenseArgs a, int32_t* nn12, float* s12) {
@@ -234,92 +342,100 @@ void dense_resolve_rows_kernel(DenseArgs a, int32_t* nn12, float* s12) {
     const int b = blockIdx.y;
     const char* d1 = a.d1 + (int64_t)b * a.d1_bstride;
     const char* d2 = a.d2 + (int64_t)b * a.d2_bstride;
+    const int32_t* list = a.lists + (int64_t)b * (a.rows_cap + a.cols_cap);
+    const int32_t* chunk_unit = a.chunk_unit + ((int64_t)b * (a.rows_cap + a.cols_cap)) / 32;
+    const int total = min(a.chunk_totals[b * 2 + 0], (int)(a.rows_cap / 32));
     const float ninf = -__builtin_inff();
-    for (int i = wave; i < a.n; i += n_waves) {
-        const u64 key = a.row_keys[(int64_t)b * a.n + i];
-        int32_t best_j = -1;
-        float best = ninf;
-        if (key != 0) {
-            const int tbase = max(0, min(key_index(key), (a.m_tiles - 1) / J)) * J;
-            const Frag q = O::load(d1 + segment_slot(i) * O::ROW_BYTES, h);
-            Frag cand[J];
+    for (int w = wave; w < total; w += n_waves) {
+        const int tbase = max(0, min(chunk_unit[w], a.row_units - 1)) * J;
+        const int i = list[(int64_t)w * 32 + c];
+        const Frag q = O::load(d1 + segment_slot(max(0, min(i, a.n - 1))) * O::ROW_BYTES, h);
+        f32x16 x[J];
+        float top = ninf;
 #pragma unroll
-            for (int jt = 0; jt < J; ++jt)
-                cand[jt] = O::load(d2 + ((int64_t)min(tbase + jt, a.m_tiles - 1) * 32 + c) * O::ROW_BYTES, h);
+        for (int jt = 0; jt < J; ++jt) {
+            const Frag cand = O::load_tile(d2 + (int64_t)min(tbase + jt, a.m_tiles - 1) * (32 * O::ROW_BYTES), c, h);
+            x[jt] = O::mma(cand, q);
 #pragma unroll
-            for (int jt = J - 1; jt >= 0; --jt) {  // descending, so that ">=" ends on the lowest tile
-                if (tbase + jt < a.m_tiles) {
-                    f32x16 x = O::mma(cand[jt], q);
-#pragma unroll
-                    for (int v = 0; v < 16; ++v)
-                        if ((tbase + jt) * 32 + tile_row(v, h) >= a.m) x[v] = ninf;
-                    float top = fold16f(ninf, x);
-                    top = __builtin_fmaxf(top, __shfl_xor(top, 32));
-                    int row = 64;
-#pragma unroll
-                    for (int v = 15; v >= 0; --v)
-                        if (x[v] == top) row = tile_row(v, h);
-                    row = min(row, __shfl_xor(row, 32));
-                    if (top >= best) {
-                        best = top;
-                        best_j = (tbase + jt) * 32 + row;
-                    }
-                }
-            }
+            for (int v = 0; v < 16; ++v)
+                if (tbase + jt >= a.m_tiles || (tbase + jt) * 32 + tile_row(v, h) >= a.m) x[jt][v] = ninf;
+            top = fold16f(top, x[jt]);
         }
-        if (lane == 0) {
-            nn12[(int64_t)b * a.n + i] = best_j;
-            if (s12) s12[(int64_t)b * a.n + i] = best;
+        top = __builtin_fmaxf(top, __shfl_xor(top, 32));
+        int row = J * 32;
+#pragma unroll
+        for (int jt = J - 1; jt >= 0; --jt)
+#pragma unroll
+            for (int v = 15; v >= 0; --v)
+                if (x[jt][v] == top) row = jt * 32 + tile_row(v, h);
+        row = min(row, __shfl_xor(row, 32));
+        if (h == 0 && i >= 0 && i < a.n) {
+            nn12[(int64_t)b * a.n + i] = row < J * 32 ? tbase * 32 + row : -1;
+            if (s12) s12[(int64_t)b * a.n + i] = top;
         }
     }
 }
 
-// Pass 2, candidates: one wave per pixel j of image 2 recomputes its scores against the S
-// consecutive queries of the winning run (j replicated into every row) and picks the lowest
-// query at the maximum.
+// Candidates: a wave takes 32 candidates whose best query lies in the same run of S queries.
+// Lane c supplies candidate list[c] as a row operand and, per part, query run0 + part*32 + c
+// as a column operand: register v of lane (c, h) is the score of that query against
+// candidate list[tile_row(v, h)].  Per candidate the maximum over the 32 lanes of a half
+// and the lowest lane that attains it (part 0 before part 1) are taken as in pass 1.
 template <int CT, int DP>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2)))
 void dense_resolve_cols_kernel(DenseArgs a, int32_t* nn21, float* s21) {
     using O = Ops<CT, DP>;
     using Frag = typename O::Frag;
-    constexpr int S = DENSE_S;
+    constexpr int S = DENSE_S, PARTS = DENSE_S / 32;
     const int lane = threadIdx.x & 63, c = lane & 31, h = lane >> 5;
     const int wave = blockIdx.x * 4 + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int n_waves = gridDim.x * 4;
     const int b = blockIdx.y;
     const char* d1 = a.d1 + (int64_t)b * a.d1_bstride;
     const char* d2 = a.d2 + (int64_t)b * a.d2_bstride;
+    const int32_t* list = a.lists + (int64_t)b * (a.rows_cap + a.cols_cap) + a.rows_cap;
+    const int32_t* chunk_unit = a.chunk_unit + ((int64_t)b * (a.rows_cap + a.cols_cap) + a.rows_cap) / 32;
+    const int total = min(a.chunk_totals[b * 2 + 1], (int)(a.cols_cap / 32));
     const float ninf = -__builtin_inff();
-    for (int j = wave; j < a.m; j += n_waves) {
-        const u64 key = a.col_keys[(int64_t)b * a.m + j];
-        int32_t best_i = -1;
-        float best = ninf;
-        if (key != 0) {
-            const int64_t run0 = (int64_t)max(0, min(key_index(key), a.n_sb * 32 - 1)) * S;  // first pixel of the run
-            const Frag cand = O::load(d2 + (int64_t)j * O::ROW_BYTES, h);
-            Frag q[S / 32];
+    for (int w = wave; w < total; w += n_waves) {
+        const int64_t run0 = (int64_t)max(0, min(chunk_unit[w], a.col_units - 1)) * S;  // first pixel of the run
+        const int j = list[(int64_t)w * 32 + c];
+        const Frag cand = O::load(d2 + (int64_t)max(0, min(j, a.m - 1)) * O::ROW_BYTES, h);
+        f32x16 x[PARTS];
 #pragma unroll
-            for (int part = 0; part < S / 32; ++part)
-                q[part] = O::load(d1 + segment_slot(run0 + part * 32 + c) * O::ROW_BYTES, h);
+        for (int part = 0; part < PARTS; ++part) {
+            const int64_t i = run0 + part * 32 + c;  // the run lies inside the padded map
+            const Frag q = O::load(d1 + segment_slot(i) * O::ROW_BYTES, h);
+            x[part] = O::mma(cand, q);
+            if (i >= a.n) {
 #pragma unroll
-            for (int part = S / 32 - 1; part >= 0; --part) {  // descending, ">=" ends on the lowest part
-                const f32x16 x = O::mma(cand, q[part]);
-                const int64_t i = run0 + part * 32 + c;
-                const float mine = i < a.n ? x[0] : ninf;      // every row of the product is candidate j
-                float top = mine;
-#pragma unroll
-                for (int mask = 1; mask < 32; mask <<= 1) top = __builtin_fmaxf(top, __shfl_xor(top, mask));
-                const u64 hit = __ballot(mine == top) & 0xFFFFFFFFull;
-                top = __shfl(top, 0);
-                if (hit && top >= best) {
-                    best = top;
-                    best_i = (int32_t)(run0 + part * 32 + (__ffsll((unsigned long long)hit) - 1));
-                }
+                for (int v = 0; v < 16; ++v) x[part][v] = ninf;
             }
         }
-        if (lane == 0) {
-            nn21[(int64_t)b * a.m + j] = best_i;
-            if (s21) s21[(int64_t)b * a.m + j] = best;
+        float mine_top = ninf;
+        int mine_first = 0;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            float y = x[0][v];
+#pragma unroll
+            for (int part = 1; part < PARTS; ++part) y = __builtin_fmaxf(y, x[part][v]);
+            const float top = half_max(y);
+            int first_lo = PARTS * 32, first_hi = PARTS * 32;
+#pragma unroll
+            for (int part = PARTS - 1; part >= 0; --part) {  // descending: ends on the lowest part
+                const u64 hit = __ballot(x[part][v] == top);
+                const unsigned lo = (unsigned)hit, hi = (unsigned)(hit >> 32);
+                if (lo) first_lo = part * 32 + __builtin_ctz(lo);
+                if (hi) first_hi = part * 32 + __builtin_ctz(hi);
+            }
+            if (tile_row(v, h) == c) {  // this lane files candidate list[c]
+                mine_top = top;
+                mine_first = h ? first_hi : first_lo;
+            }
+        }
+        if (h == ((c >> 2) & 1) && j >= 0 && j < a.m) {
+            nn21[(int64_t)b * a.m + j] = mine_first < PARTS * 32 ? (int32_t)(run0 + mine_first) : -1;
+            if (s21) s21[(int64_t)b * a.m + j] = mine_top;
         }
     }
 }
@@ -406,12 +522,20 @@ static hipError_t launch_dense_t(const DenseArgs& a, int batch, int32_t* nn12, f
                              DENSE_WAVES * 32 * sizeof(float);  // row keys, column keys, 32 maxima per wave
     hipError_t e = launch(TK_DENSE, dense_kernel<CT, DP>, grid, dim3(DENSE_WAVES * 64), lds_bytes, s, a);
     if (e != hipSuccess) return e;
-    const int cap = 8192 / batch > 64 ? 8192 / batch : 64;
-    int wgs = (a.n + 3) / 4;
+    const int most = a.n > a.m ? a.n : a.m;
+    const dim3 bucket_grid((most + BUCKET_THREADS - 1) / BUCKET_THREADS, batch);
+    e = launch(TK_DENSE_RESOLVE, dense_bucket_count_kernel, bucket_grid, dim3(BUCKET_THREADS), 0, s, a);
+    if (e != hipSuccess) return e;
+    e = launch(TK_DENSE_RESOLVE, dense_bucket_scan_kernel, dim3(2, batch), dim3(BUCKET_THREADS), 0, s, a);
+    if (e != hipSuccess) return e;
+    e = launch(TK_DENSE_RESOLVE, dense_bucket_fill_kernel, bucket_grid, dim3(BUCKET_THREADS), 0, s, a, nn12, s12, nn21, s21);
+    if (e != hipSuccess) return e;
+    const int cap = 4096 / batch > 64 ? 4096 / batch : 64;
+    int wgs = (int)((a.rows_cap / 32 + 3) / 4);
     if (wgs > cap) wgs = cap;
     e = launch(TK_DENSE_RESOLVE, dense_resolve_rows_kernel<CT, DP>, dim3(wgs, batch), dim3(256), 0, s, a, nn12, s12);
     if (e != hipSuccess) return e;
-    wgs = (a.m + 3) / 4;
+    wgs = (int)((a.cols_cap / 32 + 3) / 4);
     if (wgs > cap) wgs = cap;
     return launch(TK_DENSE_RESOLVE, dense_resolve_cols_kernel<CT, DP>, dim3(wgs, batch), dim3(256), 0, s, a, nn21, s21);
 }

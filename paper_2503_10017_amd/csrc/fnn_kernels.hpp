@@ -136,6 +136,16 @@ struct DenseArgs {
     u64* col_keys;         // [batch][m] zero-initialised; (best score, run of DENSE_S queries)
     int32_t sb_per_wg;     // super-blocks swept by one workgroup
     int32_t groups_per_wg; // candidate groups (DENSE_WAVES x DENSE_J tiles) per workgroup
+    // pass 2: pixels bucketed by their winning unit
+    int32_t row_units;     // groups of DENSE_J candidate tiles
+    int32_t col_units;     // runs of DENSE_S queries (n_sb * 32)
+    int64_t rows_cap;      // list positions for the queries: round_up(n, 32) + 32 * row_units
+    int64_t cols_cap;      // list positions for the candidates: round_up(m, 32) + 32 * col_units
+    int32_t* unit_counts;  // [batch][row_units + col_units] zero-initialised
+    int32_t* unit_cursor;  // [batch][row_units + col_units]
+    int32_t* lists;        // [batch][rows_cap + cols_cap] pixels grouped by unit, -1 padding
+    int32_t* chunk_unit;   // [batch][(rows_cap + cols_cap) / 32] unit of every chunk of 32 list positions
+    int32_t* chunk_totals; // [batch][2] chunks in use per side
 };
 // Pass 1 (both maxima with coarse locations) and pass 2 (exact indices and scores into
 // nn12/s12/nn21/s21; s12, s21 may be NULL).
