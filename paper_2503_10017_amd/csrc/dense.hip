@@ -229,7 +229,7 @@ void dense_kernel(DenseArgs a) {
 // whose order inside a bucket does not matter); a wave then takes 32 pixels of ONE unit,
 // reads the unit once and resolves all 32 with full 32x32 products -- the same matrix
 // instruction on the same operands as pass 1, so every score has the bits pass 1 saw.
-// Buckets are padded to whole chunks of 32 with -1.
+// Buckets start on chunk boundaries; the tail of a bucket's last chunk is masked off.
 constexpr int BUCKET_THREADS = 1024;
 
 __device__ __forceinline__ int row_unit_of(const DenseArgs& a, u64 key) {
@@ -239,23 +239,51 @@ __device__ __forceinline__ int col_unit_of(const DenseArgs& a, u64 key) {
     return max(0, min(key_index(key), a.col_units - 1));
 }
 
+// Bucket sizes.  LOCAL: the workgroup first counts its BUCKET_PER_THREAD * 1024 pixels of each
+// image into a histogram in LDS and then adds only the non-empty bins to the global counters
+// (device-wide atomics are slow; this cuts them several times).  Without LOCAL (more units
+// than fit in LDS) every pixel updates the global counters directly.
+constexpr int BUCKET_PER_THREAD = 16;
+
+template <bool LOCAL>
 __global__ __launch_bounds__(BUCKET_THREADS) void dense_bucket_count_kernel(DenseArgs a) {
+    extern __shared__ int hist[];
     const int b = blockIdx.y;
-    const int i = blockIdx.x * BUCKET_THREADS + threadIdx.x;
-    int32_t* counts = a.unit_counts + (int64_t)b * (a.row_units + a.col_units);
-    if (i < a.n) {
-        const u64 key = a.row_keys[(int64_t)b * a.n + i];
-        if (key) atomicAdd(&counts[row_unit_of(a, key)], 1);
+    const int units = a.row_units + a.col_units;
+    int32_t* counts = a.unit_counts + (int64_t)b * units;
+    if (LOCAL) {
+        for (int u = threadIdx.x; u < units; u += BUCKET_THREADS) hist[u] = 0;
+        __syncthreads();
     }
-    if (i < a.m) {
-        const u64 key = a.col_keys[(int64_t)b * a.m + i];
-        if (key) atomicAdd(&counts[a.row_units + col_unit_of(a, key)], 1);
+    constexpr int PER = LOCAL ? BUCKET_PER_THREAD : 1;
+    const int64_t first = (int64_t)blockIdx.x * PER * BUCKET_THREADS + threadIdx.x;
+#pragma unroll
+    for (int k = 0; k < PER; ++k) {
+        const int64_t i = first + (int64_t)k * BUCKET_THREADS;
+        if (i < a.n) {
+            const u64 key = a.row_keys[(int64_t)b * a.n + i];
+            if (key) atomicAdd(LOCAL ? &hist[row_unit_of(a, key)] : &counts[row_unit_of(a, key)], 1);
+        }
+        if (i < a.m) {
+            const u64 key = a.col_keys[(int64_t)b * a.m + i];
+            if (key) atomicAdd(LOCAL ? &hist[a.row_units + col_unit_of(a, key)] : &counts[a.row_units + col_unit_of(a, key)], 1);
+        }
+    }
+    if (LOCAL) {
+        __syncthreads();
+        for (int u = threadIdx.x; u < units; u += BUCKET_THREADS) {
+            const int c = hist[u];
+            if (c) atomicAdd(&counts[u], c);
+        }
     }
 }
 
 // blockIdx.x = side (0: queries by tile group, 1: candidates by run), blockIdx.y = pair.
-// Exclusive scan of the bucket sizes rounded up to chunks of 32; writes each bucket's first
-// list position (the fill cursor), the unit of every chunk, the -1 padding and the chunk total.
+// Exclusive scan of the bucket sizes rounded up to chunks of 32: every thread takes a run of
+// consecutive units, so one pass over the counters and one block-wide scan suffice.  Writes
+// each bucket's first list position (the fill cursor), the unit of every chunk and the chunk
+// total.  List positions between a bucket's last pixel and the end of its last chunk stay
+// unwritten; the resolve kernels know the fill level of a bucket from its cursor.
 __global__ __launch_bounds__(BUCKET_THREADS) void dense_bucket_scan_kernel(DenseArgs a) {
     __shared__ int wave_sums[BUCKET_THREADS / 64];
     const int side = blockIdx.x, b = blockIdx.y;
@@ -264,64 +292,93 @@ __global__ __launch_bounds__(BUCKET_THREADS) void dense_bucket_scan_kernel(Dense
     const int64_t list0 = side ? a.rows_cap : 0;
     const int32_t* counts = a.unit_counts + (int64_t)b * (a.row_units + a.col_units) + unit0;
     int32_t* cursor = a.unit_cursor + (int64_t)b * (a.row_units + a.col_units) + unit0;
-    int32_t* list = a.lists + (int64_t)b * (a.rows_cap + a.cols_cap) + list0;
     int32_t* chunk_unit = a.chunk_unit + ((int64_t)b * (a.rows_cap + a.cols_cap) + list0) / 32;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    int running = 0;  // chunks before this round of units
-    for (int start = 0; start < n_units; start += BUCKET_THREADS) {
-        const int u = start + (int)threadIdx.x;
-        const int count = u < n_units ? counts[u] : 0;
-        const int chunks = (count + 31) / 32;
-        int x = chunks;
+    const int per = (n_units + BUCKET_THREADS - 1) / BUCKET_THREADS;
+    const int u0 = min((int)threadIdx.x * per, n_units), u1 = min(u0 + per, n_units);
+    int mine = 0;  // chunks of this thread's units
+    for (int u = u0; u < u1; ++u) mine += (counts[u] + 31) / 32;
+    int x = mine;
 #pragma unroll
-        for (int d = 1; d < 64; d <<= 1) {
-            const int y = __shfl_up(x, d);
-            if (lane >= d) x += y;
-        }
-        __syncthreads();
-        if (lane == 63) wave_sums[wave] = x;
-        __syncthreads();
-        int offset = 0, sum = 0;
-        for (int w = 0; w < BUCKET_THREADS / 64; ++w) {
-            if (w < wave) offset += wave_sums[w];
-            sum += wave_sums[w];
-        }
-        const int first = running + offset + x - chunks;  // first chunk of this unit
-        if (u < n_units) {
-            cursor[u] = first * 32;
-            for (int k = 0; k < chunks; ++k) chunk_unit[first + k] = u;
-            for (int p = first * 32 + count; p < (first + chunks) * 32; ++p) list[p] = -1;
-        }
-        running += sum;
+    for (int d = 1; d < 64; d <<= 1) {
+        const int y = __shfl_up(x, d);
+        if (lane >= d) x += y;
     }
-    if (threadIdx.x == 0) a.chunk_totals[b * 2 + side] = running;
+    if (lane == 63) wave_sums[wave] = x;
+    __syncthreads();
+    int offset = 0, total = 0;
+    for (int w = 0; w < BUCKET_THREADS / 64; ++w) {
+        if (w < wave) offset += wave_sums[w];
+        total += wave_sums[w];
+    }
+    int first = offset + x - mine;  // first chunk of unit u0
+    for (int u = u0; u < u1; ++u) {
+        const int chunks = (counts[u] + 31) / 32;
+        cursor[u] = first * 32;
+        for (int k = 0; k < chunks; ++k) chunk_unit[first + k] = u;
+        first += chunks;
+    }
+    if (threadIdx.x == 0) a.chunk_totals[b * 2 + side] = total;
 }
 
-// Every pixel takes the next free position of its bucket.  A pixel without a key (no
-// candidate at all) gets its final "none" result here.
+// Every pixel takes the next free position of its bucket.  LOCAL: positions are first handed
+// out inside the workgroup (LDS), then each non-empty bin reserves its share of the bucket
+// with ONE global atomic.  A pixel without a key (no candidate at all) gets its final "none"
+// result here.
+template <bool LOCAL>
 __global__ __launch_bounds__(BUCKET_THREADS) void dense_bucket_fill_kernel(DenseArgs a, int32_t* nn12, float* s12,
                                                                            int32_t* nn21, float* s21) {
+    extern __shared__ int hist[];
     const int b = blockIdx.y;
-    const int i = blockIdx.x * BUCKET_THREADS + threadIdx.x;
-    int32_t* cursor = a.unit_cursor + (int64_t)b * (a.row_units + a.col_units);
+    const int units = a.row_units + a.col_units;
+    int32_t* cursor = a.unit_cursor + (int64_t)b * units;
     int32_t* list = a.lists + (int64_t)b * (a.rows_cap + a.cols_cap);
-    if (i < a.n) {
-        const u64 key = a.row_keys[(int64_t)b * a.n + i];
-        if (key) {
-            list[atomicAdd(&cursor[row_unit_of(a, key)], 1)] = i;
-        } else {
-            nn12[(int64_t)b * a.n + i] = -1;
-            if (s12) s12[(int64_t)b * a.n + i] = -__builtin_inff();
+    if (LOCAL) {
+        for (int u = threadIdx.x; u < units; u += BUCKET_THREADS) hist[u] = 0;
+        __syncthreads();
+    }
+    constexpr int PER = LOCAL ? BUCKET_PER_THREAD : 1;
+    const int64_t first = (int64_t)blockIdx.x * PER * BUCKET_THREADS + threadIdx.x;
+    int unit_r[PER], rank_r[PER], unit_c[PER], rank_c[PER];  // unit < 0: nothing to file
+#pragma unroll
+    for (int k = 0; k < PER; ++k) {
+        const int64_t i = first + (int64_t)k * BUCKET_THREADS;
+        unit_r[k] = unit_c[k] = -1;
+        rank_r[k] = rank_c[k] = 0;
+        if (i < a.n) {
+            const u64 key = a.row_keys[(int64_t)b * a.n + i];
+            if (key) {
+                unit_r[k] = row_unit_of(a, key);
+                rank_r[k] = atomicAdd(LOCAL ? &hist[unit_r[k]] : &cursor[unit_r[k]], 1);
+            } else {
+                nn12[(int64_t)b * a.n + i] = -1;
+                if (s12) s12[(int64_t)b * a.n + i] = -__builtin_inff();
+            }
+        }
+        if (i < a.m) {
+            const u64 key = a.col_keys[(int64_t)b * a.m + i];
+            if (key) {
+                unit_c[k] = a.row_units + col_unit_of(a, key);
+                rank_c[k] = atomicAdd(LOCAL ? &hist[unit_c[k]] : &cursor[unit_c[k]], 1);
+            } else {
+                nn21[(int64_t)b * a.m + i] = -1;
+                if (s21) s21[(int64_t)b * a.m + i] = -__builtin_inff();
+            }
         }
     }
-    if (i < a.m) {
-        const u64 key = a.col_keys[(int64_t)b * a.m + i];
-        if (key) {
-            list[a.rows_cap + atomicAdd(&cursor[a.row_units + col_unit_of(a, key)], 1)] = i;
-        } else {
-            nn21[(int64_t)b * a.m + i] = -1;
-            if (s21) s21[(int64_t)b * a.m + i] = -__builtin_inff();
+    if (LOCAL) {
+        __syncthreads();
+        for (int u = threadIdx.x; u < units; u += BUCKET_THREADS) {
+            const int c = hist[u];
+            if (c) hist[u] = atomicAdd(&cursor[u], c);  // first position of this workgroup's share
         }
+        __syncthreads();
+    }
+#pragma unroll
+    for (int k = 0; k < PER; ++k) {
+        const int64_t i = first + (int64_t)k * BUCKET_THREADS;
+        if (unit_r[k] >= 0) list[(LOCAL ? hist[unit_r[k]] : 0) + rank_r[k]] = (int32_t)i;
+        if (unit_c[k] >= 0) list[a.rows_cap + (LOCAL ? hist[unit_c[k]] : 0) + rank_c[k]] = (int32_t)i;
     }
 }
 
@@ -344,11 +401,13 @@ void dense_resolve_rows_kernel(DenseArgs a, int32_t* nn12, float* s12) {
     const char* d2 = a.d2 + (int64_t)b * a.d2_bstride;
     const int32_t* list = a.lists + (int64_t)b * (a.rows_cap + a.cols_cap);
     const int32_t* chunk_unit = a.chunk_unit + ((int64_t)b * (a.rows_cap + a.cols_cap)) / 32;
+    const int32_t* cursor = a.unit_cursor + (int64_t)b * (a.row_units + a.col_units);  // after the fill: end of bucket
     const int total = min(a.chunk_totals[b * 2 + 0], (int)(a.rows_cap / 32));
     const float ninf = -__builtin_inff();
     for (int w = wave; w < total; w += n_waves) {
-        const int tbase = max(0, min(chunk_unit[w], a.row_units - 1)) * J;
-        const int i = list[(int64_t)w * 32 + c];
+        const int unit = max(0, min(chunk_unit[w], a.row_units - 1));
+        const int tbase = unit * J;
+        const int i = w * 32 + c < cursor[unit] ? list[(int64_t)w * 32 + c] : -1;  // past the bucket's fill level
         const Frag q = O::load(d1 + segment_slot(max(0, min(i, a.n - 1))) * O::ROW_BYTES, h);
         f32x16 x[J];
         float top = ninf;
@@ -395,11 +454,13 @@ void dense_resolve_cols_kernel(DenseArgs a, int32_t* nn21, float* s21) {
     const char* d2 = a.d2 + (int64_t)b * a.d2_bstride;
     const int32_t* list = a.lists + (int64_t)b * (a.rows_cap + a.cols_cap) + a.rows_cap;
     const int32_t* chunk_unit = a.chunk_unit + ((int64_t)b * (a.rows_cap + a.cols_cap) + a.rows_cap) / 32;
+    const int32_t* cursor = a.unit_cursor + (int64_t)b * (a.row_units + a.col_units) + a.row_units;
     const int total = min(a.chunk_totals[b * 2 + 1], (int)(a.cols_cap / 32));
     const float ninf = -__builtin_inff();
     for (int w = wave; w < total; w += n_waves) {
-        const int64_t run0 = (int64_t)max(0, min(chunk_unit[w], a.col_units - 1)) * S;  // first pixel of the run
-        const int j = list[(int64_t)w * 32 + c];
+        const int unit = max(0, min(chunk_unit[w], a.col_units - 1));
+        const int64_t run0 = (int64_t)unit * S;  // first pixel of the run
+        const int j = w * 32 + c < cursor[unit] ? list[(int64_t)w * 32 + c] : -1;  // past the bucket's fill level
         const Frag cand = O::load(d2 + (int64_t)max(0, min(j, a.m - 1)) * O::ROW_BYTES, h);
         f32x16 x[PARTS];
 #pragma unroll
@@ -523,12 +584,23 @@ static hipError_t launch_dense_t(const DenseArgs& a, int batch, int32_t* nn12, f
     hipError_t e = launch(TK_DENSE, dense_kernel<CT, DP>, grid, dim3(DENSE_WAVES * 64), lds_bytes, s, a);
     if (e != hipSuccess) return e;
     const int most = a.n > a.m ? a.n : a.m;
-    const dim3 bucket_grid((most + BUCKET_THREADS - 1) / BUCKET_THREADS, batch);
-    e = launch(TK_DENSE_RESOLVE, dense_bucket_count_kernel, bucket_grid, dim3(BUCKET_THREADS), 0, s, a);
+    const size_t hist_bytes = ((size_t)a.row_units + a.col_units) * sizeof(int);
+    const bool local = hist_bytes <= 64 * 1024;  // the bucket histogram fits in LDS
+    const int per_wg = BUCKET_THREADS * (local ? BUCKET_PER_THREAD : 1);
+    const dim3 bucket_grid((most + per_wg - 1) / per_wg, batch);
+    if (local)
+        e = launch(TK_DENSE_RESOLVE, dense_bucket_count_kernel<true>, bucket_grid, dim3(BUCKET_THREADS), hist_bytes, s, a);
+    else
+        e = launch(TK_DENSE_RESOLVE, dense_bucket_count_kernel<false>, bucket_grid, dim3(BUCKET_THREADS), 0, s, a);
     if (e != hipSuccess) return e;
     e = launch(TK_DENSE_RESOLVE, dense_bucket_scan_kernel, dim3(2, batch), dim3(BUCKET_THREADS), 0, s, a);
     if (e != hipSuccess) return e;
-    e = launch(TK_DENSE_RESOLVE, dense_bucket_fill_kernel, bucket_grid, dim3(BUCKET_THREADS), 0, s, a, nn12, s12, nn21, s21);
+    if (local)
+        e = launch(TK_DENSE_RESOLVE, dense_bucket_fill_kernel<true>, bucket_grid, dim3(BUCKET_THREADS), hist_bytes, s, a,
+                   nn12, s12, nn21, s21);
+    else
+        e = launch(TK_DENSE_RESOLVE, dense_bucket_fill_kernel<false>, bucket_grid, dim3(BUCKET_THREADS), 0, s, a, nn12,
+                   s12, nn21, s21);
     if (e != hipSuccess) return e;
     const int cap = 4096 / batch > 64 ? 4096 / batch : 64;
     int wgs = (int)((a.rows_cap / 32 + 3) / 4);

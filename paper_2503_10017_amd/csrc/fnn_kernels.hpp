@@ -142,8 +142,8 @@ struct DenseArgs {
     int64_t rows_cap;      // list positions for the queries: round_up(n, 32) + 32 * row_units
     int64_t cols_cap;      // list positions for the candidates: round_up(m, 32) + 32 * col_units
     int32_t* unit_counts;  // [batch][row_units + col_units] zero-initialised
-    int32_t* unit_cursor;  // [batch][row_units + col_units]
-    int32_t* lists;        // [batch][rows_cap + cols_cap] pixels grouped by unit, -1 padding
+    int32_t* unit_cursor;  // [batch][row_units + col_units] next free list position (after the fill: end) of a bucket
+    int32_t* lists;        // [batch][rows_cap + cols_cap] pixels grouped by unit, buckets start on multiples of 32
     int32_t* chunk_unit;   // [batch][(rows_cap + cols_cap) / 32] unit of every chunk of 32 list positions
     int32_t* chunk_totals; // [batch][2] chunks in use per side
 };
