@@ -177,6 +177,7 @@ int32_t fnn_reciprocal(int32_t batch, const fnn_map* d1, const fnn_map* d2,
  *                (int32[batch][min(n,m)][2], entries past n_pairs[b] are -1)
  * Every S[i][j] is computed once and feeds both directions, so nn12 and nn21 are consistent
  * with each other.  s12, s21 may be NULL.
+ * n and m may not exceed 2^30 here (FNN_E_SHAPE).
  */
 int32_t fnn_mutual_dense(int32_t batch, const fnn_map* d1, const fnn_map* d2, const fnn_opts* opts,
                          int32_t* nn12, float* s12, int32_t* nn21, float* s21,

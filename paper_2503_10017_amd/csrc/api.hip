@@ -10,6 +10,7 @@ using namespace fnn;
 namespace {
 
 constexpr int64_t MAX_PIXELS = 2147483647LL - 64;
+constexpr int64_t MAX_DENSE_PIXELS = 1LL << 30;  // keeps the padded bucket lists of the dense mode within int32
 constexpr size_t WS_ALIGN = 256;
 
 struct Carver {
@@ -469,6 +470,7 @@ int32_t fnn_mutual_dense(int32_t batch, const fnn_map* d1, const fnn_map* d2, co
     const int64_t n = d1[0].n, m = d2[0].n;
     const int32_t d = d1[0].d;
     if (d2[0].d != d) return FNN_E_SHAPE;
+    if (n > MAX_DENSE_PIXELS || m > MAX_DENSE_PIXELS) return FNN_E_SHAPE;
     const int32_t de = row_channels(d, opts);
     if (de < 0) return FNN_E_SHAPE;
     if (!n_pairs) return FNN_E_NULL;

@@ -149,6 +149,8 @@ def test_reciprocal_and_dense_argument_errors(lib):
     assert dense(outs=0) == 1
     assert dense(n_pairs=0) == 1
     assert dense(d2=ctypes.cast(_map(d=8), vp)) == 2
+    big = ctypes.cast(_map(n=(1 << 30) + 1), vp)
+    assert dense(d1=big, d2=big) == 2                                   # the dense mode stops at 2^30 pixels
     assert dense(opts=_opts(compute=-1)) == 3
     assert dense(ws=0) == 5
 
