@@ -10,16 +10,18 @@
 // that one tile per query to name the lowest candidate index attaining the score.
 //
 // Work split (decided on the device from the live query count, so the host never needs to
-// read it back): the queries form row groups of R*32, the candidate tiles are cut into
-// chunks, one wave takes one (row group, chunk) unit and merges its result into the packed
-// keys with a 64-bit atomic max (score first, lowest index on ties).
+// read it back): the queries form row groups of G*R*32, the candidate tiles are cut into
+// chunks, one wave takes one (row group, chunk) unit -- every candidate tile it loads meets
+// G groups of R query blocks, a group past the live queries is skipped -- and merges its
+// result into the packed keys with a 64-bit atomic max (score first, lowest index on ties).
 #include "fnn_device.hpp"
 #include "fnn_kernels.hpp"
 #include "trace.hpp"
 
 namespace fnn {
 
-constexpr int SEARCH_R = 4;           // 32-query blocks resident per wave
+constexpr int SEARCH_R = 4;           // 32-query blocks whose products are in flight together
+constexpr int SEARCH_G = 2;           // groups of R blocks resident per wave: every candidate tile meets G*R query blocks
 constexpr int SEARCH_MIN_TILES = 4;   // shortest chunk worth a wave
 constexpr int SEARCH_WAVES = 4;       // waves per workgroup
 constexpr int SEARCH_P = 4;           // candidate tiles in flight per wave
@@ -73,7 +75,8 @@ void search_kernel(SearchArgs a) {
     if (a.nq_active) n_act = min(max(a.nq_active[b], 0), a.nq);
     if (n_act <= 0 || a.m_tiles <= 0) return;
 
-    const int row_groups = (n_act + 32 * R - 1) / (32 * R);
+    constexpr int G = SEARCH_G;
+    const int row_groups = (n_act + 32 * R * G - 1) / (32 * R * G);
     int chunks = max(1, n_waves / row_groups);
     int tiles_per_chunk = max((a.m_tiles + chunks - 1) / chunks, SEARCH_MIN_TILES);
     chunks = (a.m_tiles + tiles_per_chunk - 1) / tiles_per_chunk;
@@ -87,7 +90,7 @@ void search_kernel(SearchArgs a) {
     for (int64_t unit = wave; unit < units; unit += n_waves) {
         const int chunk = (int)(unit / row_groups);
         const int rg = (int)(unit % row_groups);
-        const int slot0 = rg * 32 * R;
+        const int slot0 = rg * 32 * R * G;
 
         const int t0 = chunk * tiles_per_chunk;
         const int t1 = min(t0 + tiles_per_chunk, a.m_tiles);
@@ -99,17 +102,23 @@ void search_kernel(SearchArgs a) {
         for (int p = 0; p < P; ++p)
             ring[p] = O::load_tile(tgt + (int64_t)min(t0 + p, t1 - 1) * (32 * O::ROW_BYTES), c, h);
 
-        // blocks past the live queries of the last row group are computed on row 0 and dropped
-        Frag q[R];
-        float best[R];
-        int best_tile[R];
+        // blocks past the live queries of the last row group are computed on row 0 and dropped;
+        // a whole group of R blocks past them is skipped
+        Frag q[G][R];
+        float best[G][R];
+        int best_tile[G][R];
+        bool live[G];
 #pragma unroll
-        for (int r = 0; r < R; ++r) {
-            const int slot = slot0 + r * 32 + c;
-            const int64_t row = slot < n_act ? query_row(a, qbase, slot) : 0;
-            q[r] = O::load(src + row * O::ROW_BYTES, h);
-            best[r] = ninf;
-            best_tile[r] = 0x7FFFFFFF;
+        for (int g = 0; g < G; ++g) {
+            live[g] = slot0 + g * 32 * R < n_act;  // uniform
+#pragma unroll
+            for (int r = 0; r < R; ++r) {
+                const int slot = slot0 + (g * R + r) * 32 + c;
+                const int64_t row = slot < n_act ? query_row(a, qbase, slot) : 0;
+                q[g][r] = O::load(src + row * O::ROW_BYTES, h);
+                best[g][r] = ninf;
+                best_tile[g][r] = 0x7FFFFFFF;
+            }
         }
 
         for (int tb = t0; tb < t1; tb += P) {
@@ -119,37 +128,44 @@ void search_kernel(SearchArgs a) {
                 if (t < t1) {  // uniform
                     const Frag cur = ring[p];
                     ring[p] = O::load_tile(tgt + (int64_t)min(t + P, t1 - 1) * (32 * O::ROW_BYTES), c, h);
-                    f32x16 acc[R];
 #pragma unroll
-                    for (int r = 0; r < R; ++r) acc[r] = O::mma(cur, q[r]);
-                    if (t * 32 + 32 > a.m) {  // only the last tile of the map can be partial
+                    for (int g = 0; g < G; ++g) {
+                        if (live[g]) {
+                            f32x16 acc[R];
 #pragma unroll
-                        for (int r = 0; r < R; ++r)
+                            for (int r = 0; r < R; ++r) acc[r] = O::mma(cur, q[g][r]);
+                            if (t * 32 + 32 > a.m) {  // only the last tile of the map can be partial
 #pragma unroll
-                            for (int v = 0; v < 16; ++v)
-                                if (t * 32 + tile_row(v, h) >= a.m) acc[r][v] = ninf;
-                    }
+                                for (int r = 0; r < R; ++r)
 #pragma unroll
-                    for (int r = 0; r < R; ++r) {
-                        const float top = fold16(best[r], acc[r]);
-                        if (top > best[r]) best_tile[r] = t;
-                        best[r] = top;
+                                    for (int v = 0; v < 16; ++v)
+                                        if (t * 32 + tile_row(v, h) >= a.m) acc[r][v] = ninf;
+                            }
+#pragma unroll
+                            for (int r = 0; r < R; ++r) {
+                                const float top = fold16(best[g][r], acc[r]);
+                                if (top > best[g][r]) best_tile[g][r] = t;
+                                best[g][r] = top;
+                            }
+                        }
                     }
                 }
             }
         }
 
 #pragma unroll
-        for (int r = 0; r < R; ++r) {
-            const float ob = __shfl_xor(best[r], 32);
-            const int ot = __shfl_xor(best_tile[r], 32);
-            if (ob > best[r] || (ob == best[r] && ot < best_tile[r])) {
-                best[r] = ob;
-                best_tile[r] = ot;
+        for (int g = 0; g < G; ++g)
+#pragma unroll
+            for (int r = 0; r < R; ++r) {
+                const float ob = __shfl_xor(best[g][r], 32);
+                const int ot = __shfl_xor(best_tile[g][r], 32);
+                if (ob > best[g][r] || (ob == best[g][r] && ot < best_tile[g][r])) {
+                    best[g][r] = ob;
+                    best_tile[g][r] = ot;
+                }
+                const int slot = slot0 + (g * R + r) * 32 + c;
+                if (h == 0 && slot < n_act) atomicMax(&a.out_keys[qbase + slot], pack_key(best[g][r], best_tile[g][r]));
             }
-            const int slot = slot0 + r * 32 + c;
-            if (h == 0 && slot < n_act) atomicMax(&a.out_keys[qbase + slot], pack_key(best[r], best_tile[r]));
-        }
     }
 }
 
@@ -224,7 +240,7 @@ static hipError_t launch_search_t(const SearchArgs& a, int batch, hipStream_t s)
     int wgs = resident_wgs / batch;
     if (wgs >= 8) wgs &= ~7;  // a multiple of 8 per pair keeps the XCD renumbering a bijection
     if (wgs < 1) wgs = 1;
-    const int64_t max_units = (int64_t)((a.nq + 32 * SEARCH_R - 1) / (32 * SEARCH_R)) *
+    const int64_t max_units = (int64_t)((a.nq + 32 * SEARCH_R * SEARCH_G - 1) / (32 * SEARCH_R * SEARCH_G)) *
                               ((a.m_tiles + SEARCH_MIN_TILES - 1) / SEARCH_MIN_TILES);
     const int64_t need = (max_units + SEARCH_WAVES - 1) / SEARCH_WAVES;
     if (need < wgs) wgs = (int)(need > 0 ? need : 1);
