@@ -58,7 +58,6 @@ struct PrepArgs {
     int32_t l2;         // append the norm channels of the L2 score (FNN_FLAG_L2)
 };
 hipError_t launch_prep(const PrepArgs& a, hipStream_t s);
-hipError_t launch_fill_u64(u64* p, int64_t count, u64 value, hipStream_t s);
 // "no neighbour": idx = -1, score = -inf (score may be NULL)
 hipError_t launch_fill_i32f32(int32_t* idx, float* score, int64_t count, hipStream_t s);
 

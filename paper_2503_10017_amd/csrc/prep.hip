@@ -201,11 +201,6 @@ static hipError_t launch_prep_fast(const PrepArgs& a, dim3 grid, hipStream_t s) 
     return launch(TK_PREP, prep_f32_kernel<GROUPS, FNN_BF16>, grid, dim3(256), 0, s, a);
 }
 
-__global__ __launch_bounds__(256) void fill_u64_kernel(u64* p, int64_t count, u64 value) {
-    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < count; i += (int64_t)gridDim.x * blockDim.x)
-        p[i] = value;
-}
-
 __global__ __launch_bounds__(256) void fill_none_kernel(int32_t* idx, float* score, int64_t count) {
     for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < count; i += (int64_t)gridDim.x * blockDim.x) {
         idx[i] = -1;
@@ -245,13 +240,6 @@ hipError_t launch_prep(const PrepArgs& a, hipStream_t s) {
         }
     }
     return launch(TK_PREP, prep_kernel, grid, dim3(256), 0, s, a);
-}
-
-hipError_t launch_fill_u64(u64* p, int64_t count, u64 value, hipStream_t s) {
-    if (count <= 0) return hipSuccess;
-    int64_t blocks = (count + 255) / 256;
-    if (blocks > 2048) blocks = 2048;
-    return launch(TK_FILL, fill_u64_kernel, dim3((unsigned)blocks), dim3(256), 0, s, p, count, value);
 }
 
 }  // namespace fnn

@@ -81,9 +81,8 @@ int32_t fnn_trace_end(int32_t capacity, int32_t* kinds, float* milliseconds, int
 const char* fnn_trace_kind_name(int32_t kind) {
     switch (kind) {
         case TK_PREP: return "prep_kernel";
-        case TK_FILL: return "fill_u64_kernel";
+        case TK_FILL: return "fill_none_kernel";
         case TK_SEARCH: return "search_kernel";
-        case TK_RECIP_INIT: return "recip_init_kernel";
         case TK_RECIP_STEP: return "recip_step_kernel";
         case TK_RECIP_DEDUP: return "recip_dedup_kernel";
         case TK_DENSE: return "dense_kernel";

@@ -11,8 +11,8 @@ enum TraceKind : int {
     TK_PREP = 0,
     TK_FILL = 1,
     TK_SEARCH = 2,
-    TK_UNUSED = 3,
-    TK_RECIP_INIT = 4,
+    TK_RESERVED_3 = 3,  // numbers are part of what fnn_trace_end reports: retired kinds keep theirs
+    TK_RESERVED_4 = 4,
     TK_RECIP_STEP = 5,
     TK_RECIP_DEDUP = 6,
     TK_DENSE = 7,
