@@ -21,7 +21,8 @@
 namespace fnn {
 
 constexpr int SEARCH_R = 4;           // 32-query blocks whose products are in flight together
-constexpr int SEARCH_G = 2;           // groups of R blocks resident per wave: every candidate tile meets G*R query blocks
+constexpr int SEARCH_G_MAX = 4;       // up to this many groups of R blocks resident per wave (G*R blocks meet every tile)
+constexpr int SEARCH_WIDE_MIN_TILES = 256;  // a wave takes more groups only while its chunk stays at least this long
 constexpr int SEARCH_MIN_TILES = 4;   // shortest chunk worth a wave
 constexpr int SEARCH_WAVES = 4;       // waves per workgroup
 constexpr int SEARCH_P = 4;           // candidate tiles in flight per wave
@@ -54,7 +55,7 @@ __device__ __forceinline__ int64_t query_row(const SearchArgs& a, int64_t qbase,
 // here carries the tile number in its index field; pass 2 turns it into the candidate index.
 // (waves_per_eu >= 2 caps the kernel at 256 registers, which lets the matrix instructions
 // write their results straight into ordinary vector registers.)
-template <int CT, int DP, int R, int P>
+template <int CT, int DP, int R, int P, int G>
 __global__ __launch_bounds__(SEARCH_WAVES * 64) __attribute__((amdgpu_waves_per_eu(2)))
 void search_kernel(SearchArgs a) {
     using O = Ops<CT, DP>;
@@ -75,7 +76,6 @@ void search_kernel(SearchArgs a) {
     if (a.nq_active) n_act = min(max(a.nq_active[b], 0), a.nq);
     if (n_act <= 0 || a.m_tiles <= 0) return;
 
-    constexpr int G = SEARCH_G;
     const int row_groups = (n_act + 32 * R * G - 1) / (32 * R * G);
     int chunks = max(1, n_waves / row_groups);
     int tiles_per_chunk = max((a.m_tiles + chunks - 1) / chunks, SEARCH_MIN_TILES);
@@ -221,6 +221,15 @@ void resolve_kernel(SearchArgs a, int32_t* out_idx, float* out_score) {
     }
 }
 
+template <int CT, int DP, int G>
+static hipError_t launch_search_g(const SearchArgs& a, int batch, int wgs, hipStream_t s) {
+    const int64_t max_units = (int64_t)((a.nq + 32 * SEARCH_R * G - 1) / (32 * SEARCH_R * G)) *
+                              ((a.m_tiles + SEARCH_MIN_TILES - 1) / SEARCH_MIN_TILES);
+    const int64_t need = (max_units + SEARCH_WAVES - 1) / SEARCH_WAVES;
+    if (need < wgs) wgs = (int)(need > 0 ? need : 1);
+    return launch(TK_SEARCH, search_kernel<CT, DP, SEARCH_R, SEARCH_P, G>, dim3(wgs, batch), dim3(SEARCH_WAVES * 64), 0, s, a);
+}
+
 template <int CT, int DP>
 static hipError_t launch_search_t(const SearchArgs& a, int batch, hipStream_t s) {
     // One resident wave per hardware slot: the grid is exactly what the chip holds at once
@@ -231,7 +240,7 @@ static hipError_t launch_search_t(const SearchArgs& a, int batch, hipStream_t s)
     if (resident_wgs == 0) {
         int per_cu = 0, dev = 0;
         hipDeviceProp_t prop;
-        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, search_kernel<CT, DP, SEARCH_R, SEARCH_P>,
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, search_kernel<CT, DP, SEARCH_R, SEARCH_P, SEARCH_G_MAX>,
                                                          SEARCH_WAVES * 64, 0) != hipSuccess ||
             hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess)
             return hipErrorUnknown;
@@ -240,11 +249,17 @@ static hipError_t launch_search_t(const SearchArgs& a, int batch, hipStream_t s)
     int wgs = resident_wgs / batch;
     if (wgs >= 8) wgs &= ~7;  // a multiple of 8 per pair keeps the XCD renumbering a bijection
     if (wgs < 1) wgs = 1;
-    const int64_t max_units = (int64_t)((a.nq + 32 * SEARCH_R * SEARCH_G - 1) / (32 * SEARCH_R * SEARCH_G)) *
-                              ((a.m_tiles + SEARCH_MIN_TILES - 1) / SEARCH_MIN_TILES);
-    const int64_t need = (max_units + SEARCH_WAVES - 1) / SEARCH_WAVES;
-    if (need < wgs) wgs = (int)(need > 0 ? need : 1);
-    return launch(TK_SEARCH, search_kernel<CT, DP, SEARCH_R, SEARCH_P>, dim3(wgs, batch), dim3(SEARCH_WAVES * 64), 0, s, a);
+    // Wider row groups (more query blocks per loaded candidate tile) pay off while the chunks
+    // stay long; with many waves per pair (few pairs) short chunks would mostly pay start-up.
+    const int n_waves = wgs * SEARCH_WAVES;
+    auto chunk_tiles = [&](int g) {
+        const int row_groups = (a.nq + 32 * SEARCH_R * g - 1) / (32 * SEARCH_R * g);
+        const int chunks = n_waves / row_groups > 0 ? n_waves / row_groups : 1;
+        return a.m_tiles / chunks;
+    };
+    if (chunk_tiles(4) >= SEARCH_WIDE_MIN_TILES) return launch_search_g<CT, DP, 4>(a, batch, wgs, s);
+    if (chunk_tiles(2) >= SEARCH_WIDE_MIN_TILES) return launch_search_g<CT, DP, 2>(a, batch, wgs, s);
+    return launch_search_g<CT, DP, 1>(a, batch, wgs, s);
 }
 
 hipError_t launch_search(const SearchArgs& a, int batch, int compute, int dp, hipStream_t s) {
