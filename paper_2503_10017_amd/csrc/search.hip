@@ -21,7 +21,8 @@
 namespace fnn {
 
 constexpr int SEARCH_R = 4;           // 32-query blocks whose products are in flight together
-constexpr int SEARCH_G_MAX = 4;       // up to this many groups of R blocks resident per wave (G*R blocks meet every tile)
+// A wave keeps G groups of R query blocks resident (G = 1, 2 or 4, chosen per launch), so every
+// candidate tile it loads meets G*R query blocks.
 constexpr int SEARCH_WIDE_MIN_TILES = 256;  // a wave takes more groups only while its chunk stays at least this long
 constexpr int SEARCH_MIN_TILES = 4;   // shortest chunk worth a wave
 constexpr int SEARCH_WAVES = 4;       // waves per workgroup
@@ -221,8 +222,48 @@ void resolve_kernel(SearchArgs a, int32_t* out_idx, float* out_score) {
     }
 }
 
+// One resident wave per hardware slot: the grid is exactly what the chip holds at once
+// (workgroups per CU from the occupancy calculator x CUs), split evenly between the pairs, so
+// there is no partial last round and the per-wave start-up cost and the final key merges are
+// paid once per slot.  Two waves per SIMD are what the widest variant fits and what measured
+// best for the narrower ones too, so the widest variant's occupancy sizes every launch.
+template <int CT, int DP>
+constexpr int search_g_limit() {
+    // a query fragment is ROW_BYTES / 8 registers per lane and G*R of them are resident
+    constexpr int frag_regs = Ops<CT, DP>::ROW_BYTES / 8;
+    return frag_regs <= 6 ? 4 : (frag_regs <= 12 ? 2 : 1);
+}
+template <int CT, int DP>
+static int search_wgs_per_pair(int batch) {
+    static int resident_wgs = 0;
+    if (resident_wgs == 0) {
+        int per_cu = 0, dev = 0;
+        hipDeviceProp_t prop;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu,
+                                                         search_kernel<CT, DP, SEARCH_R, SEARCH_P, search_g_limit<CT, DP>()>,
+                                                         SEARCH_WAVES * 64, 0) != hipSuccess ||
+            hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess)
+            return 0;
+        resident_wgs = (per_cu > 0 ? per_cu : 1) * prop.multiProcessorCount;
+    }
+    int wgs = resident_wgs / batch;
+    if (wgs >= 8) wgs &= ~7;  // a multiple of 8 per pair keeps the XCD renumbering a bijection
+    return wgs < 1 ? 1 : wgs;
+}
+
+// Tiles per chunk if the launch used row groups of G*R blocks.
 template <int CT, int DP, int G>
-static hipError_t launch_search_g(const SearchArgs& a, int batch, int wgs, hipStream_t s) {
+static int search_chunk_tiles(const SearchArgs& a, int batch) {
+    const int n_waves = search_wgs_per_pair<CT, DP>(batch) * SEARCH_WAVES;
+    const int row_groups = (a.nq + 32 * SEARCH_R * G - 1) / (32 * SEARCH_R * G);
+    const int chunks = n_waves / row_groups > 0 ? n_waves / row_groups : 1;
+    return a.m_tiles / chunks;
+}
+
+template <int CT, int DP, int G>
+static hipError_t launch_search_g(const SearchArgs& a, int batch, hipStream_t s) {
+    int wgs = search_wgs_per_pair<CT, DP>(batch);
+    if (wgs == 0) return hipErrorUnknown;
     const int64_t max_units = (int64_t)((a.nq + 32 * SEARCH_R * G - 1) / (32 * SEARCH_R * G)) *
                               ((a.m_tiles + SEARCH_MIN_TILES - 1) / SEARCH_MIN_TILES);
     const int64_t need = (max_units + SEARCH_WAVES - 1) / SEARCH_WAVES;
@@ -232,34 +273,15 @@ static hipError_t launch_search_g(const SearchArgs& a, int batch, int wgs, hipSt
 
 template <int CT, int DP>
 static hipError_t launch_search_t(const SearchArgs& a, int batch, hipStream_t s) {
-    // One resident wave per hardware slot: the grid is exactly what the chip holds at once
-    // (workgroups per CU from the occupancy calculator x CUs), split evenly between the
-    // pairs, so there is no partial last round and the per-wave start-up cost and the final
-    // key merges are paid once per slot.
-    static int resident_wgs = 0;
-    if (resident_wgs == 0) {
-        int per_cu = 0, dev = 0;
-        hipDeviceProp_t prop;
-        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, search_kernel<CT, DP, SEARCH_R, SEARCH_P, SEARCH_G_MAX>,
-                                                         SEARCH_WAVES * 64, 0) != hipSuccess ||
-            hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess)
-            return hipErrorUnknown;
-        resident_wgs = (per_cu > 0 ? per_cu : 1) * prop.multiProcessorCount;
-    }
-    int wgs = resident_wgs / batch;
-    if (wgs >= 8) wgs &= ~7;  // a multiple of 8 per pair keeps the XCD renumbering a bijection
-    if (wgs < 1) wgs = 1;
     // Wider row groups (more query blocks per loaded candidate tile) pay off while the chunks
-    // stay long; with many waves per pair (few pairs) short chunks would mostly pay start-up.
-    const int n_waves = wgs * SEARCH_WAVES;
-    auto chunk_tiles = [&](int g) {
-        const int row_groups = (a.nq + 32 * SEARCH_R * g - 1) / (32 * SEARCH_R * g);
-        const int chunks = n_waves / row_groups > 0 ? n_waves / row_groups : 1;
-        return a.m_tiles / chunks;
-    };
-    if (chunk_tiles(4) >= SEARCH_WIDE_MIN_TILES) return launch_search_g<CT, DP, 4>(a, batch, wgs, s);
-    if (chunk_tiles(2) >= SEARCH_WIDE_MIN_TILES) return launch_search_g<CT, DP, 2>(a, batch, wgs, s);
-    return launch_search_g<CT, DP, 1>(a, batch, wgs, s);
+    // stay long -- with many waves per pair (few pairs) short chunks would mostly pay
+    // start-up -- and while the resident query fragments fit the register file.
+    constexpr int G_LIMIT = search_g_limit<CT, DP>();
+    if constexpr (G_LIMIT >= 4)
+        if (search_chunk_tiles<CT, DP, 4>(a, batch) >= SEARCH_WIDE_MIN_TILES) return launch_search_g<CT, DP, 4>(a, batch, s);
+    if constexpr (G_LIMIT >= 2)
+        if (search_chunk_tiles<CT, DP, 2>(a, batch) >= SEARCH_WIDE_MIN_TILES) return launch_search_g<CT, DP, 2>(a, batch, s);
+    return launch_search_g<CT, DP, 1>(a, batch, s);
 }
 
 hipError_t launch_search(const SearchArgs& a, int batch, int compute, int dp, hipStream_t s) {
