@@ -60,6 +60,8 @@ def main() -> int:
     ap.add_argument("--latency", action="store_true", help="also time a single pair (adds search launches)")
     ap.add_argument("--contrast", action="store_true",
                     help="also time the paper's blocked schedules (Algorithms 1 and 2 with a materialised score block)")
+    ap.add_argument("--normalize", action="store_true",
+                    help="also time the same batch with the L2 normalisation of raw head outputs fused into the prepare pass")
     ap.add_argument("--l2", action="store_true",
                     help="also time the same batch with the squared-distance dist_func (FNN_FLAG_L2)")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -218,6 +220,25 @@ def main() -> int:
         dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
+
+    # ---- optional: the same batch as raw head outputs (normalisation fused into the prepare pass) --
+    if args.normalize:
+        nout = fnn.fnn_reciprocal(d1, d2, seeds, MAX_ITER, compute, normalize=True, workspace=ws)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            fnn.fnn_reciprocal(d1, d2, seeds, MAX_ITER, compute, out=nout, normalize=True, workspace=ws)
+        torch.cuda.synchronize()
+        n_s = (time.perf_counter() - t0) / args.steps
+        fnn.fnn_trace_begin(64)  # one more step with per-kernel events, for the prepare kernel's own duration
+        fnn.fnn_reciprocal(d1, d2, seeds, MAX_ITER, compute, out=nout, normalize=True, workspace=ws)
+        torch.cuda.synchronize()
+        prep = [ms for name, ms in fnn.fnn_trace_end(64) if name == "prep_kernel"]
+        result["normalize_variant"] = {
+            "ms_per_step": round(n_s * 1e3, 4), "pairs_per_s": round(BATCH / n_s, 2),
+            "prep_kernel_ms": round(sum(prep) / max(len(prep), 1), 4),
+            "note": "same 16 pairs with FNN_FLAG_NORMALIZE: norm, division and cast in one pass over the fp32 maps",
+        }
 
     # ---- optional: the same batch with dist_func = squared distance ------------------------------
     if args.l2:

@@ -158,6 +158,55 @@ __global__ __launch_bounds__(256) void prep_f32_kernel(PrepArgs a) {
     constexpr int ESIZE = (COMPUTE == FNN_F32) ? 4 : 2;
     char* dst = reinterpret_cast<char*>(sd.dst) + (int64_t)b * sd.n_pad * (GROUPS * 8) * ESIZE;
     const float* src = reinterpret_cast<const float*>(sd.src[b]);
+    if (a.normalize) {
+        // One thread per row: the row is read once with 16-byte loads and its norm is formed in
+        // registers (channels ascending, squares and sums rounded separately, as descriptor_norm).
+        for (uint32_t row = blockIdx.x * blockDim.x + threadIdx.x; row < (uint32_t)sd.n_pad; row += gridDim.x * blockDim.x) {
+            const int64_t pix = sd.segment_major ? slot_pixel(row) : (int64_t)row;
+            float v[GROUPS * 8];
+#pragma unroll
+            for (int e = 0; e < GROUPS * 8; ++e) v[e] = 0.0f;
+            if (pix < sd.n) {
+                const float4* p = reinterpret_cast<const float4*>(src + pix * sd.row_stride);
+#pragma unroll
+                for (int q = 0; q < GROUPS * 2; ++q) {
+                    const float4 x = p[q];
+                    v[4 * q + 0] = x.x;
+                    v[4 * q + 1] = x.y;
+                    v[4 * q + 2] = x.z;
+                    v[4 * q + 3] = x.w;
+                }
+                float sum = 0.0f;
+#pragma unroll
+                for (int e = 0; e < GROUPS * 8; ++e) sum = __fadd_rn(sum, __fmul_rn(v[e], v[e]));
+                const float norm = __fsqrt_rn(sum);
+                if (norm > 0.0f) {
+#pragma unroll
+                    for (int e = 0; e < GROUPS * 8; ++e) v[e] = __fdiv_rn(v[e], norm);
+                }
+            }
+            if (COMPUTE == FNN_F32) {
+                float4* out = reinterpret_cast<float4*>(dst + (int64_t)row * (GROUPS * 8) * 4);
+#pragma unroll
+                for (int q = 0; q < GROUPS * 2; ++q) out[q] = make_float4(v[4 * q], v[4 * q + 1], v[4 * q + 2], v[4 * q + 3]);
+            } else {
+                uint4* out = reinterpret_cast<uint4*>(dst + (int64_t)row * (GROUPS * 8) * 2);
+#pragma unroll
+                for (int q = 0; q < GROUPS; ++q) {
+                    uint32_t w[4];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const float lo = v[8 * q + 2 * e], hi = v[8 * q + 2 * e + 1];
+                        const uint32_t l16 = (COMPUTE == FNN_F16) ? float_to_f16_rne(lo) : float_to_bf16_rne(lo);
+                        const uint32_t h16 = (COMPUTE == FNN_F16) ? float_to_f16_rne(hi) : float_to_bf16_rne(hi);
+                        w[e] = l16 | (h16 << 16);
+                    }
+                    out[q] = make_uint4(w[0], w[1], w[2], w[3]);
+                }
+            }
+        }
+        return;
+    }
     for (uint32_t item = blockIdx.x * blockDim.x + threadIdx.x; item < total; item += gridDim.x * blockDim.x) {
         const uint32_t row = item / GROUPS;
         const uint32_t g = item - row * GROUPS;
@@ -167,13 +216,6 @@ __global__ __launch_bounds__(256) void prep_f32_kernel(PrepArgs a) {
             const float4* p = reinterpret_cast<const float4*>(src + pix * sd.row_stride + g * 8);
             lo = p[0];
             hi = p[1];
-            if (a.normalize) {
-                const float norm = descriptor_norm(src, pix * sd.row_stride, a.d, FNN_F32);
-                if (norm > 0.0f) {
-                    lo = make_float4(__fdiv_rn(lo.x, norm), __fdiv_rn(lo.y, norm), __fdiv_rn(lo.z, norm), __fdiv_rn(lo.w, norm));
-                    hi = make_float4(__fdiv_rn(hi.x, norm), __fdiv_rn(hi.y, norm), __fdiv_rn(hi.z, norm), __fdiv_rn(hi.w, norm));
-                }
-            }
         }
         if (COMPUTE == FNN_F32) {
             float4* out = reinterpret_cast<float4*>(dst + ((int64_t)item * 8) * 4);
