@@ -144,6 +144,96 @@ __global__ __launch_bounds__(256) void prep_kernel(PrepArgs a) {
     }
 }
 
+// Fast path for the options that need a whole row at once (FNN_FLAG_NORMALIZE, FNN_FLAG_L2) on
+// fp32 sources with d a multiple of 8: one thread per row.  The row is read once with 16-byte
+// loads; norm and squared length are formed in registers exactly as descriptor_norm and
+// minus_half_norm2 define them (channels ascending, every product and sum rounded on its own).
+// IN = d / 8, OUT = dp / 8.
+template <int IN, int OUT, int COMPUTE>
+__global__ __launch_bounds__(256) void prep_rows_f32_kernel(PrepArgs a) {
+    prep_side_jobs(a);
+    const int side_idx = blockIdx.y / a.batch;
+    const int b = blockIdx.y % a.batch;
+    const PrepSide& sd = a.side[side_idx];
+    constexpr int ESIZE = (COMPUTE == FNN_F32) ? 4 : 2;
+    constexpr int D = IN * 8, DP = OUT * 8;
+    constexpr int EXTRA = (COMPUTE == FNN_F32) ? 1 : 2;  // channels per L2 term
+    char* dst = reinterpret_cast<char*>(sd.dst) + (int64_t)b * sd.n_pad * DP * ESIZE;
+    const float* src = reinterpret_cast<const float*>(sd.src[b]);
+    for (uint32_t row = blockIdx.x * blockDim.x + threadIdx.x; row < (uint32_t)sd.n_pad; row += gridDim.x * blockDim.x) {
+        const int64_t pix = sd.segment_major ? slot_pixel(row) : (int64_t)row;
+        float v[DP];
+#pragma unroll
+        for (int e = 0; e < DP; ++e) v[e] = 0.0f;
+        if (pix < sd.n) {
+            const float4* p = reinterpret_cast<const float4*>(src + pix * sd.row_stride);
+#pragma unroll
+            for (int q = 0; q < IN * 2; ++q) {
+                const float4 x = p[q];
+                v[4 * q + 0] = x.x;
+                v[4 * q + 1] = x.y;
+                v[4 * q + 2] = x.z;
+                v[4 * q + 3] = x.w;
+            }
+            if (a.normalize) {
+                float sum = 0.0f;
+#pragma unroll
+                for (int e = 0; e < D; ++e) sum = __fadd_rn(sum, __fmul_rn(v[e], v[e]));
+                const float norm = __fsqrt_rn(sum);
+                if (norm > 0.0f) {
+#pragma unroll
+                    for (int e = 0; e < D; ++e) v[e] = __fdiv_rn(v[e], norm);
+                }
+            }
+#pragma unroll
+            for (int e = 0; e < D; ++e) v[e] = round_to_compute(v[e], COMPUTE);
+            if (a.l2) {
+                float sum = 0.0f;
+#pragma unroll
+                for (int e = 0; e < D; ++e) sum = __fadd_rn(sum, __fmul_rn(v[e], v[e]));
+                const float term = -0.5f * sum;
+                const float hi = round_to_compute(term, COMPUTE);
+                const float lo = round_to_compute(term - hi, COMPUTE);
+                const int ones0 = D + (sd.second_image ? EXTRA : 0);
+                const int term0 = D + (sd.second_image ? 0 : EXTRA);
+#pragma unroll
+                for (int e = D; e < D + 2 * EXTRA; ++e) {
+                    if (e >= ones0 && e < ones0 + EXTRA) v[e] = 1.0f;
+                    if (e == term0) v[e] = hi;
+                    if (EXTRA == 2 && e == term0 + 1) v[e] = lo;
+                }
+            }
+        }
+        if (COMPUTE == FNN_F32) {
+            float4* out = reinterpret_cast<float4*>(dst + (int64_t)row * DP * 4);
+#pragma unroll
+            for (int q = 0; q < OUT * 2; ++q) out[q] = make_float4(v[4 * q], v[4 * q + 1], v[4 * q + 2], v[4 * q + 3]);
+        } else {
+            uint4* out = reinterpret_cast<uint4*>(dst + (int64_t)row * DP * 2);
+#pragma unroll
+            for (int q = 0; q < OUT; ++q) {
+                uint32_t w[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    // the values are already representable: the conversion is exact
+                    const float lo = v[8 * q + 2 * e], hi = v[8 * q + 2 * e + 1];
+                    const uint32_t l16 = (COMPUTE == FNN_F16) ? float_to_f16_rne(lo) : float_to_bf16_rne(lo);
+                    const uint32_t h16 = (COMPUTE == FNN_F16) ? float_to_f16_rne(hi) : float_to_bf16_rne(hi);
+                    w[e] = l16 | (h16 << 16);
+                }
+                out[q] = make_uint4(w[0], w[1], w[2], w[3]);
+            }
+        }
+    }
+}
+
+template <int IN, int OUT>
+static hipError_t launch_prep_rows(const PrepArgs& a, dim3 grid, hipStream_t s) {
+    if (a.compute == FNN_F32) return launch(TK_PREP, prep_rows_f32_kernel<IN, OUT, FNN_F32>, grid, dim3(256), 0, s, a);
+    if (a.compute == FNN_F16) return launch(TK_PREP, prep_rows_f32_kernel<IN, OUT, FNN_F16>, grid, dim3(256), 0, s, a);
+    return launch(TK_PREP, prep_rows_f32_kernel<IN, OUT, FNN_BF16>, grid, dim3(256), 0, s, a);
+}
+
 // Fast path: fp32 source whose rows are whole 16-byte vectors and need no channel padding
 // (d == dp).  GROUPS = dp / 8 is a compile-time constant so that the row / group split of the
 // item index costs a multiply, and every thread moves two 16-byte loads into one (16-bit
@@ -158,55 +248,6 @@ __global__ __launch_bounds__(256) void prep_f32_kernel(PrepArgs a) {
     constexpr int ESIZE = (COMPUTE == FNN_F32) ? 4 : 2;
     char* dst = reinterpret_cast<char*>(sd.dst) + (int64_t)b * sd.n_pad * (GROUPS * 8) * ESIZE;
     const float* src = reinterpret_cast<const float*>(sd.src[b]);
-    if (a.normalize) {
-        // One thread per row: the row is read once with 16-byte loads and its norm is formed in
-        // registers (channels ascending, squares and sums rounded separately, as descriptor_norm).
-        for (uint32_t row = blockIdx.x * blockDim.x + threadIdx.x; row < (uint32_t)sd.n_pad; row += gridDim.x * blockDim.x) {
-            const int64_t pix = sd.segment_major ? slot_pixel(row) : (int64_t)row;
-            float v[GROUPS * 8];
-#pragma unroll
-            for (int e = 0; e < GROUPS * 8; ++e) v[e] = 0.0f;
-            if (pix < sd.n) {
-                const float4* p = reinterpret_cast<const float4*>(src + pix * sd.row_stride);
-#pragma unroll
-                for (int q = 0; q < GROUPS * 2; ++q) {
-                    const float4 x = p[q];
-                    v[4 * q + 0] = x.x;
-                    v[4 * q + 1] = x.y;
-                    v[4 * q + 2] = x.z;
-                    v[4 * q + 3] = x.w;
-                }
-                float sum = 0.0f;
-#pragma unroll
-                for (int e = 0; e < GROUPS * 8; ++e) sum = __fadd_rn(sum, __fmul_rn(v[e], v[e]));
-                const float norm = __fsqrt_rn(sum);
-                if (norm > 0.0f) {
-#pragma unroll
-                    for (int e = 0; e < GROUPS * 8; ++e) v[e] = __fdiv_rn(v[e], norm);
-                }
-            }
-            if (COMPUTE == FNN_F32) {
-                float4* out = reinterpret_cast<float4*>(dst + (int64_t)row * (GROUPS * 8) * 4);
-#pragma unroll
-                for (int q = 0; q < GROUPS * 2; ++q) out[q] = make_float4(v[4 * q], v[4 * q + 1], v[4 * q + 2], v[4 * q + 3]);
-            } else {
-                uint4* out = reinterpret_cast<uint4*>(dst + (int64_t)row * (GROUPS * 8) * 2);
-#pragma unroll
-                for (int q = 0; q < GROUPS; ++q) {
-                    uint32_t w[4];
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        const float lo = v[8 * q + 2 * e], hi = v[8 * q + 2 * e + 1];
-                        const uint32_t l16 = (COMPUTE == FNN_F16) ? float_to_f16_rne(lo) : float_to_bf16_rne(lo);
-                        const uint32_t h16 = (COMPUTE == FNN_F16) ? float_to_f16_rne(hi) : float_to_bf16_rne(hi);
-                        w[e] = l16 | (h16 << 16);
-                    }
-                    out[q] = make_uint4(w[0], w[1], w[2], w[3]);
-                }
-            }
-        }
-        return;
-    }
     for (uint32_t item = blockIdx.x * blockDim.x + threadIdx.x; item < total; item += gridDim.x * blockDim.x) {
         const uint32_t row = item / GROUPS;
         const uint32_t g = item - row * GROUPS;
@@ -267,12 +308,23 @@ hipError_t launch_prep(const PrepArgs& a, hipStream_t s) {
     int64_t blocks = (most + 255) / 256;
     if (blocks > 4096) blocks = 4096;
     dim3 grid((unsigned)blocks, (unsigned)(a.n_sides * a.batch));
-    bool fast = a.d == a.dp && !a.l2 && most < (int64_t)1 << 31;
-    for (int i = 0; i < a.n_sides && fast; ++i) {
+    bool vector_rows = most < (int64_t)1 << 31;  // fp32 sources whose rows are whole, aligned 16-byte vectors
+    for (int i = 0; i < a.n_sides && vector_rows; ++i) {
         const PrepSide& sd = a.side[i];
-        fast = sd.dtype == FNN_F32 && sd.row_stride % 4 == 0;
-        for (int b = 0; b < a.batch && fast; ++b) fast = ((uintptr_t)sd.src[b] % 16) == 0;
+        vector_rows = sd.dtype == FNN_F32 && sd.row_stride % 4 == 0;
+        for (int b = 0; b < a.batch && vector_rows; ++b) vector_rows = ((uintptr_t)sd.src[b] % 16) == 0;
     }
+    if (vector_rows && (a.normalize || a.l2) && a.d % 8 == 0) {
+        const int in = a.d / 8, out = a.dp / 8;
+        if (in == 1 && out == 1) return launch_prep_rows<1, 1>(a, grid, s);
+        if (in == 1 && out == 2) return launch_prep_rows<1, 2>(a, grid, s);
+        if (in == 2 && out == 2) return launch_prep_rows<2, 2>(a, grid, s);
+        if (in == 2 && out == 3) return launch_prep_rows<2, 3>(a, grid, s);
+        if (in == 3 && out == 3) return launch_prep_rows<3, 3>(a, grid, s);
+        if (in == 3 && out == 4) return launch_prep_rows<3, 4>(a, grid, s);
+        if (in == 4 && out == 4) return launch_prep_rows<4, 4>(a, grid, s);
+    }
+    const bool fast = vector_rows && a.d == a.dp && !a.l2 && !a.normalize;
     if (fast) {
         switch (a.dp / 8) {
             case 1: return launch_prep_fast<1>(a, grid, s);
