@@ -1,0 +1,45 @@
+"""The search launcher picks how many query blocks a wave keeps resident (1, 2 or 4 groups of four) from the
+batch size, the query count and the candidate count.  These shapes are chosen to reach each choice on an
+MI355X (64 pairs leave 32 waves per pair; a wave takes more groups only while its chunk keeps >= 256 tiles);
+whatever is chosen, the results must be bit-identical to single-pair calls (which use one group) and to the oracle.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2503_10017_amd as fnn
+from gpu_helpers import dev, exact_maps, host
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.mark.parametrize("nq,m,compute,l2", [
+    (128, 262144 + 17, "f16", False),     # 8192 tiles / 32 chunks = 256 per chunk: four groups
+    (512, 160000, "f16", False),          # 5000 tiles: 156 per chunk with four groups, 312 with two
+    (512, 160000, "bf16", True),          # 32-channel rows: at most two groups
+    (128, 100000, "f32", False),          # fp32 rows of 24 channels: at most two groups (195 tiles per chunk: one)
+    (512, 40000, "f16", False),           # short chunks: one group
+])
+def test_every_row_group_width_gives_the_same_answers(nq, m, compute, l2):
+    batch, n, d = 64, 2048, 24
+    _, cand = exact_maps(900 + nq, 1, m, d)
+    tb = dev(cand)
+    rng = np.random.default_rng(nq + m)
+    srcs = [rng.integers(-8, 9, size=(n, d)).astype(np.float32) / 8 for _ in range(batch)]
+    q = np.stack([np.sort(rng.choice(n, nq, replace=False)) for _ in range(batch)]).astype(np.int32)
+    ts = [dev(x) for x in srcs]
+    gi, gs = fnn.fnn_nearest(ts, [tb] * batch, q_idx=dev(q), compute=compute, l2=l2)
+    torch.cuda.synchronize()
+    gi, gs = host(gi), host(gs)
+    for b in (0, 17, 63):                  # single-pair calls: many waves per pair, one group per wave
+        si, ss = fnn.fnn_nearest(ts[b], tb, q_idx=dev(q[b])[None], compute=compute, l2=l2)
+        torch.cuda.synchronize()
+        assert np.array_equal(gi[b], host(si)[0]) and np.array_equal(gs[b], host(ss)[0])
+    for b in (0, 63):
+        if l2:
+            ri, rbest, _ = oracle.nearest_l2(srcs[b][q[b]], cand)
+            assert np.array_equal(gi[b], ri) and np.array_equal(-2.0 * gs[b], rbest)
+        else:
+            ri, rbest, _ = oracle.nearest(srcs[b][q[b]], cand)
+            assert np.array_equal(gi[b], ri) and np.array_equal(gs[b], rbest)
