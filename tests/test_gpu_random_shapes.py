@@ -1,0 +1,77 @@
+"""Seeded sweep over small random shapes and options for all three entry points, on exactly representable
+maps (entries k/8), so every comparison with the oracle is bit for bit: ragged sizes around the tile (32),
+row-group (128) and super-block (2048) boundaries, every compute format, both dist_funcs, d from 1 to 32,
+batches, repeated and unordered query indices."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2503_10017_amd as fnn
+from gpu_helpers import check_reciprocal_exact, dev, host
+
+pytestmark = pytest.mark.gpu
+
+SIZES = [1, 2, 31, 32, 33, 63, 64, 65, 127, 128, 129, 255, 257, 1000, 2047, 2048, 2049, 4100]
+
+
+def draw(rng):
+    compute = ["f16", "bf16", "f32"][rng.integers(0, 3)]
+    l2 = bool(rng.integers(0, 2))
+    d_max = (30 if compute == "f32" else 28) if l2 else 32
+    d = int(rng.integers(1, d_max + 1))
+    n, m = (int(SIZES[rng.integers(0, len(SIZES))]) for _ in range(2))
+    batch = int(rng.integers(1, 4))
+    return compute, l2, d, n, m, batch
+
+
+def maps(rng, batch, n, d):
+    return [rng.integers(-8, 9, size=(n, d)).astype(np.float32) / 8 for _ in range(batch)]
+
+
+@pytest.mark.parametrize("case", range(24))
+def test_nearest_random_case(case):
+    rng = np.random.default_rng(7000 + case)
+    compute, l2, d, n, m, batch = draw(rng)
+    a, b = maps(rng, batch, n, d), maps(rng, batch, m, d)
+    nq = int(rng.integers(1, 2 * n + 2))
+    q = rng.integers(0, n, size=(batch, nq)).astype(np.int32)          # repeats, any order, possibly more than n
+    gi, gs = fnn.fnn_nearest([dev(x) for x in a], [dev(x) for x in b], q_idx=dev(q), compute=compute, l2=l2)
+    torch.cuda.synchronize()
+    for p in range(batch):
+        if l2:
+            ri, rbest, _ = oracle.nearest_l2(a[p][q[p]], b[p])
+            assert np.array_equal(host(gi)[p], ri) and np.array_equal(-2.0 * host(gs)[p], rbest), (compute, l2, d, n, m, batch)
+        else:
+            ri, rbest, _ = oracle.nearest(a[p][q[p]], b[p])
+            assert np.array_equal(host(gi)[p], ri) and np.array_equal(host(gs)[p], rbest), (compute, l2, d, n, m, batch)
+
+
+@pytest.mark.parametrize("case", range(16))
+def test_reciprocal_and_dense_random_case(case):
+    rng = np.random.default_rng(8000 + case)
+    compute, l2, d, n, m, batch = draw(rng)
+    metric = "l2" if l2 else "dot"
+    a, b = maps(rng, batch, n, d), maps(rng, batch, m, d)
+    n_seeds = int(rng.integers(1, min(n, 300) + 1))
+    seeds = np.stack([rng.choice(n, n_seeds, replace=False) for _ in range(batch)]).astype(np.int32)
+    max_iter = int(rng.integers(0, 6))
+    ta, tb = [dev(x) for x in a], [dev(x) for x in b]
+    out = fnn.fnn_reciprocal(ta, tb, dev(seeds), max_iter=max_iter, compute=compute, l2=l2)
+    dense = fnn.fnn_mutual_dense(ta, tb, compute=compute, l2=l2)
+    torch.cuda.synchronize()
+    got = {k: host(v) for k, v in out.items()}
+    dn = {k: host(v) for k, v in dense.items()}
+    scale = 2.0 if l2 else 1.0                                          # the library reports -1/2 of the squared distance
+    for p in range(batch):
+        what = (compute, l2, d, n, m, batch, max_iter, p)
+        if max_iter > 0:
+            check_reciprocal_exact(got, p, oracle.reciprocal(a[p], b[p], seeds[p], max_iter, metric=metric))
+        else:                                                           # no iteration: nothing converges, V^0 is reported
+            vi, _, _ = (oracle.nearest_l2 if l2 else oracle.nearest)(a[p][seeds[p]], b[p])
+            assert np.array_equal(got["seed_j"][p], vi) and (got["seed_iter"][p] == -1).all() and got["n_pairs"][p] == 0, what
+        ref = oracle.mutual_dense(a[p], b[p], metric=metric)
+        assert np.array_equal(dn["nn12"][p], ref["nn12"]) and np.array_equal(dn["nn21"][p], ref["nn21"]), what
+        assert np.array_equal(scale * dn["s12"][p], ref["s12"]) and np.array_equal(scale * dn["s21"][p], ref["s21"]), what
+        k = int(dn["n_pairs"][p])
+        assert np.array_equal(dn["pairs"][p, :k], ref["pairs"]) and np.all(dn["pairs"][p, k:] == -1), what
