@@ -56,6 +56,7 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--compute", default="f16", choices=["f16", "bf16", "f32"])
     ap.add_argument("--no-dense", action="store_true", help="skip the dense mutual-NN leg")
+    ap.add_argument("--no-cfg5", action="store_true", help="skip the 1024x768 bf16 leg (configs[4]: dense mutual NN + reciprocal)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--latency", action="store_true", help="also time a single pair (adds search launches)")
     ap.add_argument("--contrast", action="store_true",
@@ -340,6 +341,42 @@ def main() -> int:
                          "avg_launch_ms": round(dense_ms, 4), "flops_per_launch": dflops,
                          "note": "algorithmic flops 2*24*N*M (a K=16 plus a K=8 matrix instruction per 32x32 block, no padding)"},
         }
+
+    # ---- the large pair (configs[4]): 1024x768, dense mutual NN in bf16, then FastNN reciprocal ------
+    if not args.no_dense and not args.no_cfg5:
+        a5, b5 = synth.config_pair(5)
+        n5 = a5.shape[0]
+        t5a, t5b = torch.from_numpy(a5).to(dev), torch.from_numpy(b5).to(dev)
+        s5 = torch.from_numpy(synth.grid_seeds(1024, 768, SUBSAMPLE)).to(dev)[None]
+        ws5 = torch.empty(fnn.fnn_workspace_bytes(1, n5, n5, D, s5.shape[1], "bf16"), dtype=torch.uint8, device=dev)
+        d5 = fnn.fnn_mutual_dense(t5a, t5b, "bf16", workspace=ws5)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(3):
+            fnn.fnn_mutual_dense(t5a, t5b, "bf16", out=d5, workspace=ws5)
+        torch.cuda.synchronize()
+        call5 = (time.perf_counter() - t0) / 3
+        fnn.fnn_trace_begin(32)
+        fnn.fnn_mutual_dense(t5a, t5b, "bf16", out=d5, workspace=ws5)
+        torch.cuda.synchronize()
+        k5 = [ms for name, ms in fnn.fnn_trace_end(32) if name == "dense_kernel"]
+        r5 = fnn.fnn_reciprocal(t5a, t5b, s5, MAX_ITER, "bf16", workspace=ws5)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(10):
+            fnn.fnn_reciprocal(t5a, t5b, s5, MAX_ITER, "bf16", out=r5, workspace=ws5)
+        torch.cuda.synchronize()
+        flops5 = 2.0 * D * n5 * n5
+        result["large_pair"] = {
+            "workload": "configs[4]: one 1024x768 D=24 pair, bf16 products / fp32 accumulate: all 786432 x 786432 scores, "
+                        "then FastNN reciprocal from 12288 seeds",
+            "dense_call_ms": round(call5 * 1e3, 3), "dense_tflops_call": round(flops5 / call5 / 1e12, 2),
+            "dense_kernel_ms": round(k5[0], 3) if k5 else None,
+            "dense_kernel_frac_of_mfma_peak": round(flops5 / (k5[0] * 1e-3) / 1e12 / PEAK_MFMA_16BIT, 4) if k5 else None,
+            "mutual_pairs": int(d5["n_pairs"][0]),
+            "reciprocal_ms": round((time.perf_counter() - t0) / 10 * 1e3, 4), "matches": int(r5["n_pairs"][0]),
+        }
+        del t5a, t5b, ws5, d5
 
     # ---- CPU oracle on a bounded sample of the same workload (baseline only) ----------------------
     if not args.no_cpu:
