@@ -510,12 +510,12 @@ int32_t fnn_mutual_dense(int32_t batch, const fnn_map* d1, const fnn_map* d2, co
     da.lists = L.lists;
     da.chunk_unit = L.chunk_unit;
     da.chunk_totals = L.chunk_totals;
-    // Workgroup tile: up to 3 query super-blocks (48 KB of LDS keys) x up to 4 candidate
-    // groups.  Larger tiles mean fewer merges into the global key tables; small problems
+    // Workgroup tile: up to 3 query super-blocks (48 KB of LDS keys) x up to 8 candidate
+    // groups (of DENSE_WAVES x DENSE_J tiles).  Larger tiles mean fewer merges into the global key tables; small problems
     // shrink the tile until the grid covers the chip a few times.
     const int64_t groups_total = (da.m_tiles + DENSE_TILES_PER_GROUP - 1) / DENSE_TILES_PER_GROUP;
     int64_t sb_per_wg = da.n_sb < 3 ? da.n_sb : 3;
-    int64_t groups_per_wg = 4;
+    int64_t groups_per_wg = 8;
     auto wg_count = [&]() {
         return ((da.n_sb + sb_per_wg - 1) / sb_per_wg) * ((groups_total + groups_per_wg - 1) / groups_per_wg) * batch;
     };

@@ -121,7 +121,7 @@ hipError_t launch_recip_dedup(const RecipState& st, int32_t n_seeds, int batch,
 
 // ---- dense mutual nearest neighbours -----------------------------------------------------
 constexpr int DENSE_J = 4;      // candidate tiles resident per wave
-constexpr int DENSE_WAVES = 8;  // waves per workgroup
+constexpr int DENSE_WAVES = 4;  // waves per workgroup
 constexpr int DENSE_TILES_PER_GROUP = DENSE_J * DENSE_WAVES;
 struct DenseArgs {
     const char* d1;        // prepared queries, segment-major, [batch][n_sb*32*DENSE_S][dp]
