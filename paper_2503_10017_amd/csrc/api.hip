@@ -510,18 +510,17 @@ int32_t fnn_mutual_dense(int32_t batch, const fnn_map* d1, const fnn_map* d2, co
     da.lists = L.lists;
     da.chunk_unit = L.chunk_unit;
     da.chunk_totals = L.chunk_totals;
-    // Workgroup tile: up to 3 query super-blocks (48 KB of LDS keys) x up to 8 candidate
-    // groups (of DENSE_WAVES x DENSE_J tiles).  Larger tiles mean fewer merges into the global key tables; small problems
-    // shrink the tile until the grid covers the chip a few times.
+    // Workgroup tile: one query super-block (32 KB of LDS keys) x up to 8 candidate groups (of
+    // DENSE_WAVES x DENSE_J tiles).  Larger tiles mean fewer merges into the global key
+    // tables; small problems shrink the tile until the grid covers the chip a few times.
     const int64_t groups_total = (da.m_tiles + DENSE_TILES_PER_GROUP - 1) / DENSE_TILES_PER_GROUP;
-    int64_t sb_per_wg = da.n_sb < 3 ? da.n_sb : 3;
+    const int64_t sb_per_wg = 1;
     int64_t groups_per_wg = 8;
     auto wg_count = [&]() {
         return ((da.n_sb + sb_per_wg - 1) / sb_per_wg) * ((groups_total + groups_per_wg - 1) / groups_per_wg) * batch;
     };
     while (groups_per_wg > 1 && wg_count() < 1024) groups_per_wg >>= 1;
-    while (sb_per_wg > 1 && wg_count() < 1024) --sb_per_wg;
-    da.sb_per_wg = (int32_t)(sb_per_wg > 0 ? sb_per_wg : 1);
+    da.sb_per_wg = (int32_t)sb_per_wg;
     da.groups_per_wg = (int32_t)groups_per_wg;
     if (n > 0 && m > 0) FNN_TRY(launch_dense(da, batch, opts->compute, L.maps.dp, nn12, s12, nn21, s21, s));
     else if (n > 0) FNN_TRY(launch_fill_i32f32(nn12, s12, (int64_t)batch * n, s));

@@ -7,7 +7,7 @@
 
 namespace fnn {
 
-constexpr int DENSE_S = 64;      // query blocks per super-block (a run is S consecutive pixels)
+constexpr int DENSE_S = 128;     // query blocks per super-block (a run is S consecutive pixels)
 
 // pixel held by lane c of block t of super-block sb
 __host__ __device__ inline int segment_pixel(int sb, int t, int c) { return sb * (32 * DENSE_S) + c * DENSE_S + t; }

@@ -1,6 +1,6 @@
 """Seeded sweep over small random shapes and options for all three entry points, on exactly representable
 maps (entries k/8), so every comparison with the oracle is bit for bit: ragged sizes around the tile (32),
-row-group (128) and super-block (2048) boundaries, every compute format, both dist_funcs, d from 1 to 32,
+row-group (128) and super-block (4096) boundaries, every compute format, both dist_funcs, d from 1 to 32,
 batches, repeated and unordered query indices."""
 import numpy as np
 import pytest
@@ -12,7 +12,7 @@ from gpu_helpers import check_reciprocal_exact, dev, host
 
 pytestmark = pytest.mark.gpu
 
-SIZES = [1, 2, 31, 32, 33, 63, 64, 65, 127, 128, 129, 255, 257, 1000, 2047, 2048, 2049, 4100]
+SIZES = [1, 2, 31, 32, 33, 63, 64, 65, 127, 128, 129, 255, 257, 1000, 2047, 2049, 4095, 4096, 4097, 8200]
 
 
 def draw(rng):
