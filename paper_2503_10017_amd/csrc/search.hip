@@ -306,7 +306,7 @@ hipError_t launch_search(const SearchArgs& a, int batch, int compute, int dp, hi
 template <int CT, int DP>
 static hipError_t launch_resolve_t(const SearchArgs& a, int batch, int32_t* out_idx, float* out_score, hipStream_t s) {
     int wgs = (a.nq + 3) / 4;
-    const int cap = 8192 / batch > 64 ? 8192 / batch : 64;
+    const int cap = 2048 / batch > 64 ? 2048 / batch : 64;  // measured best: more waves only add dispatch time
     if (wgs > cap) wgs = cap;
     return launch(TK_RESOLVE, resolve_kernel<CT, DP>, dim3(wgs, batch), dim3(256), 0, s, a, out_idx, out_score);
 }
