@@ -243,7 +243,7 @@ __device__ __forceinline__ int col_unit_of(const DenseArgs& a, u64 key) {
 // image into a histogram in LDS and then adds only the non-empty bins to the global counters
 // (device-wide atomics are slow; this cuts them several times).  Without LOCAL (more units
 // than fit in LDS) every pixel updates the global counters directly.
-constexpr int BUCKET_PER_THREAD = 16;
+constexpr int BUCKET_PER_THREAD = 4;
 
 template <bool LOCAL>
 __global__ __launch_bounds__(BUCKET_THREADS) void dense_bucket_count_kernel(DenseArgs a) {
