@@ -53,8 +53,8 @@ __device__ __forceinline__ void dense_sweep(const DenseArgs& a, const typename O
     using Frag = typename O::Frag;
     constexpr int J = DENSE_J, S = DENSE_S;
     const float ninf = -__builtin_inff();
-    Frag qa = O::load(qbase, h);
-    Frag qb = O::load(qbase + 32 * O::ROW_BYTES, h);
+    Frag qa = O::load_tile(qbase, c, h);
+    Frag qb = O::load_tile(qbase + 32 * O::ROW_BYTES, c, h);
     // Software pipeline: the matrix instructions of the NEXT product pair are issued before
     // the current pair's 32 result registers are folded, so the matrix cores stay busy while
     // the vector ALU works.
@@ -67,8 +67,8 @@ __device__ __forceinline__ void dense_sweep(const DenseArgs& a, const typename O
     for (int t = 0; t < S; t += 2) {
         // prefetch the next two query blocks (the last step reloads its own)
         const int tn = min(t + 2, S - 2);
-        const Frag na = O::load(qbase + (int64_t)tn * 32 * O::ROW_BYTES, h);
-        const Frag nb = O::load(qbase + (int64_t)(tn + 1) * 32 * O::ROW_BYTES, h);
+        const Frag na = O::load_tile(qbase + (int64_t)tn * 32 * O::ROW_BYTES, c, h);
+        const Frag nb = O::load_tile(qbase + (int64_t)(tn + 1) * 32 * O::ROW_BYTES, c, h);
         float ra = ninf, rb = ninf;
 #pragma unroll
         for (int jt = 0; jt < J; ++jt) {
@@ -169,7 +169,7 @@ void dense_kernel(DenseArgs a) {
 #pragma unroll
                 for (int v = 0; v < 16; ++v) cmax[jt][v] = ninf;
 
-            const char* qbase = d1 + ((int64_t)sbg * S * 32 + c) * O::ROW_BYTES;
+            const char* qbase = d1 + (int64_t)sbg * S * 32 * O::ROW_BYTES;  // uniform: the lane offset is added by load_tile
             if (cand_tail || query_tail)
                 dense_sweep<CT, DP, true>(a, cand, cmax, qbase, sbg, tbase, lds_row_keys + sb * S * 32, tbase / J, c, h);
             else
