@@ -42,3 +42,20 @@ def test_nearest_beyond_two_gib_of_candidates():
     assert (ri >= strong_from).mean() > 0.9                           # the case is exercised
     assert np.array_equal(gi, ri)
     assert np.array_equal(gs, rbest)
+
+
+def test_dense_with_more_bucket_units_than_fit_in_lds():
+    # 2.2 million query pixels make more than 16384 runs of 128 queries: the second pass of the dense mode
+    # then buckets with direct global atomics instead of its LDS histograms.  Few candidates keep it cheap.
+    n, m, d = 2_200_003, 100, 8
+    rng = np.random.default_rng(77)
+    a = rng.integers(-8, 9, size=(n, d)).astype(np.float32) / 8
+    b = rng.integers(-8, 9, size=(m, d)).astype(np.float32) / 8
+    assert (n + 4095) // 4096 * 32 > 16384
+    out = fnn.fnn_mutual_dense(dev(a), dev(b), compute="f16")
+    torch.cuda.synchronize()
+    ref = oracle.mutual_dense(a, b)
+    assert np.array_equal(host(out["nn12"])[0], ref["nn12"]) and np.array_equal(host(out["s12"])[0], ref["s12"])
+    assert np.array_equal(host(out["nn21"])[0], ref["nn21"]) and np.array_equal(host(out["s21"])[0], ref["s21"])
+    k = int(host(out["n_pairs"])[0])
+    assert np.array_equal(host(out["pairs"])[0, :k], ref["pairs"])
