@@ -35,6 +35,14 @@
  *    A call may be captured into a HIP graph (it launches kernels only, clears its buffers with
  *    kernels and never synchronises) once the same entry point has run eagerly on the device,
  *    which fills the launch-shape caches.
+ *  - The maps are read by the enqueued work and never written: keep them alive and unchanged
+ *    until the stream has passed the call.  fnn_nearest and fnn_reciprocal copy a map into the
+ *    workspace (cast to the compute format, rows padded) unless the caller's array already
+ *    is what that copy would be -- stored in the compute format, d in {16, 24, 32} (16-bit
+ *    formats) or a multiple of 8 (FNN_F32), row_stride == d, n a multiple of 32, 16-byte
+ *    aligned, the batch's maps equally spaced in memory, no flags -- in which case it is
+ *    searched where it is and that side costs no copy.  Results do not depend on which way
+ *    a map took.
  *  - Errors are return codes only.  Argument errors are detected on the host before
  *    anything is enqueued (outputs untouched).  Index arrays live in device memory and are
  *    NOT range-checked: a seed or query index outside [0, n) is undefined behaviour.

@@ -174,16 +174,47 @@ void fill_prep_side(PrepSide& sd, int32_t batch, const fnn_map* maps, int64_t n_
     sd.dst = dst;
 }
 
+// A batch of caller maps that already has the layout the kernels read: stored in the compute
+// format, dp channels per row, rows packed, whole 32-pixel tiles, 16-byte aligned, and the
+// pairs equally spaced in memory (one stacked array).  Such maps are used where they are.
+bool direct_layout(int32_t batch, const fnn_map* maps, const fnn_opts* opts, int dp, const char** base, int64_t* bstride) {
+    const fnn_map& m0 = maps[0];
+    if (opts->flags != 0) return false;
+    for (int b = 0; b < batch; ++b)
+        if (maps[b].dtype != opts->compute || maps[b].d != dp || maps[b].row_stride != dp || maps[b].n != m0.n) return false;
+    if (m0.n <= 0 || m0.n % 32 != 0 || ((uintptr_t)m0.data % 16) != 0) return false;
+    const int64_t bytes = m0.n * dp * elem_size(opts->compute);
+    int64_t stride = 0;
+    if (batch > 1) {
+        stride = (const char*)maps[1].data - (const char*)m0.data;
+        if (stride < bytes || stride % 16 != 0) return false;
+        for (int b = 2; b < batch; ++b)
+            if ((const char*)maps[b].data != (const char*)m0.data + (int64_t)b * stride) return false;
+    }
+    *base = (const char*)m0.data;
+    *bstride = stride;
+    return true;
+}
+
+// Prepares the maps that are not used in place (skip_a / skip_b) and runs the side jobs.
 hipError_t prep_both(int32_t batch, const fnn_map* a, const fnn_map* b, const MapsLayout& L, int d, const fnn_opts* opts,
-                     hipStream_t s, const PrepExtra& extra, bool first_segment_major = false) {
+                     hipStream_t s, const PrepExtra& extra, bool first_segment_major = false, bool skip_a = false,
+                     bool skip_b = false) {
     const int compute = opts->compute;
     PrepArgs pa;
     memset(&pa, 0, sizeof(pa));
     pa.extra = extra;
-    fill_prep_side(pa.side[0], batch, a, L.n_pad, L.p1, 0);
-    pa.side[0].segment_major = first_segment_major ? 1 : 0;
-    fill_prep_side(pa.side[1], batch, b, L.m_pad, L.p2, 1);
-    pa.n_sides = 2;
+    int sides = 0;
+    if (!skip_a) {
+        fill_prep_side(pa.side[sides], batch, a, L.n_pad, L.p1, 0);
+        pa.side[sides].segment_major = first_segment_major ? 1 : 0;
+        ++sides;
+    }
+    if (!skip_b) {
+        fill_prep_side(pa.side[sides], batch, b, L.m_pad, L.p2, 1);
+        ++sides;
+    }
+    pa.n_sides = sides;
     pa.batch = batch;
     pa.d = d;
     pa.dp = L.dp;
@@ -280,17 +311,21 @@ int32_t fnn_nearest(int32_t batch, const fnn_map* src, const int32_t* q_idx, int
     memset(&extra, 0, sizeof(extra));
     extra.zero_ptr = L.keys;  // the key table starts empty
     extra.zero_count = (int64_t)batch * nq;
-    FNN_TRY(prep_both(batch, src, tgt, L.maps, d, opts, s, extra));
+    const char *p1 = (const char*)L.maps.p1, *p2 = (const char*)L.maps.p2;
+    int64_t bs1 = L.maps.bstride1, bs2 = L.maps.bstride2;
+    const bool direct1 = direct_layout(batch, src, opts, L.maps.dp, &p1, &bs1);
+    const bool direct2 = direct_layout(batch, tgt, opts, L.maps.dp, &p2, &bs2);
+    FNN_TRY(prep_both(batch, src, tgt, L.maps, d, opts, s, extra, false, direct1, direct2));
     SearchArgs sa;
     memset(&sa, 0, sizeof(sa));
-    sa.src = (const char*)L.maps.p1;
-    sa.src_bstride = L.maps.bstride1;
+    sa.src = p1;
+    sa.src_bstride = bs1;
     sa.src_rows = (int32_t)L.maps.n_pad;
     sa.q_idx = q_idx;
     sa.nq_active = nq_active;
     sa.nq = (int32_t)nq;
-    sa.tgt = (const char*)L.maps.p2;
-    sa.tgt_bstride = L.maps.bstride2;
+    sa.tgt = p2;
+    sa.tgt_bstride = bs2;
     sa.m = (int32_t)m;
     sa.m_tiles = (int32_t)(L.maps.m_pad / 32);
     sa.out_keys = L.keys;
@@ -405,31 +440,35 @@ int32_t fnn_reciprocal(int32_t batch, const fnn_map* d1, const fnn_map* d2, cons
     extra.seed_id = L.st.seed_id[0];
     extra.n_active = L.st.n_active;
     extra.n_seeds = ns;
-    FNN_TRY(prep_both(batch, d1, d2, L.maps, d, opts, s, extra));
+    const char *p1 = (const char*)L.maps.p1, *p2 = (const char*)L.maps.p2;
+    int64_t bs1 = L.maps.bstride1, bs2 = L.maps.bstride2;
+    const bool direct1 = direct_layout(batch, d1, opts, L.maps.dp, &p1, &bs1);
+    const bool direct2 = direct_layout(batch, d2, opts, L.maps.dp, &p2, &bs2);
+    FNN_TRY(prep_both(batch, d1, d2, L.maps, d, opts, s, extra, false, direct1, direct2));
 
     SearchArgs fwd;  // queries in image 1 -> candidates in image 2
     memset(&fwd, 0, sizeof(fwd));
-    fwd.src = (const char*)L.maps.p1;
-    fwd.src_bstride = L.maps.bstride1;
+    fwd.src = p1;
+    fwd.src_bstride = bs1;
     fwd.src_rows = (int32_t)L.maps.n_pad;
     fwd.nq_active = L.st.n_active;
     fwd.nq = ns;
-    fwd.tgt = (const char*)L.maps.p2;
-    fwd.tgt_bstride = L.maps.bstride2;
+    fwd.tgt = p2;
+    fwd.tgt_bstride = bs2;
     fwd.m = (int32_t)m;
     fwd.m_tiles = (int32_t)(L.maps.m_pad / 32);
     fwd.out_keys = L.st.keys_f;
 
     SearchArgs bwd;  // queries in image 2 (named by the index field of keys_f) -> image 1
     memset(&bwd, 0, sizeof(bwd));
-    bwd.src = (const char*)L.maps.p2;
-    bwd.src_bstride = L.maps.bstride2;
+    bwd.src = p2;
+    bwd.src_bstride = bs2;
     bwd.src_rows = (int32_t)L.maps.m_pad;
     bwd.q_keys = L.st.keys_f;
     bwd.nq_active = L.st.n_active;
     bwd.nq = ns;
-    bwd.tgt = (const char*)L.maps.p1;
-    bwd.tgt_bstride = L.maps.bstride1;
+    bwd.tgt = p1;
+    bwd.tgt_bstride = bs1;
     bwd.m = (int32_t)n;
     bwd.m_tiles = (int32_t)(L.maps.n_pad / 32);
     bwd.out_keys = L.st.keys_b;

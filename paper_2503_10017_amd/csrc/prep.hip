@@ -298,13 +298,24 @@ hipError_t launch_fill_i32f32(int32_t* idx, float* score, int64_t count, hipStre
     return launch(TK_FILL, fill_none_kernel, dim3((unsigned)blocks), dim3(256), 0, s, idx, score, count);
 }
 
+// The side jobs alone.
+__global__ __launch_bounds__(256) void init_kernel(PrepArgs a) { prep_side_jobs(a); }
+
 hipError_t launch_prep(const PrepArgs& a, hipStream_t s) {
     int64_t most = 0;
     for (int i = 0; i < a.n_sides; ++i) {
         const int64_t items = a.side[i].n_pad * (a.dp / 8);
         if (items > most) most = items;
     }
-    if (most == 0) return hipSuccess;
+    if (most == 0) {
+        // no map to convert (empty, or all used in place): only the side jobs, if any
+        int64_t work = a.extra.zero_ptr ? a.extra.zero_count : 0;
+        if (a.extra.seeds && (int64_t)a.batch * a.extra.n_seeds > work) work = (int64_t)a.batch * a.extra.n_seeds;
+        if (work <= 0) return hipSuccess;
+        int64_t init_blocks = (work + 255) / 256;
+        if (init_blocks > 1024) init_blocks = 1024;
+        return launch(TK_PREP, init_kernel, dim3((unsigned)init_blocks, 1), dim3(256), 0, s, a);
+    }
     int64_t blocks = (most + 255) / 256;
     if (blocks > 4096) blocks = 4096;
     dim3 grid((unsigned)blocks, (unsigned)(a.n_sides * a.batch));
