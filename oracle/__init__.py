@@ -131,10 +131,39 @@ def nearest_l2(a: np.ndarray, b: np.ndarray):
     return idx, best, second
 
 
+def split_fp16(x: np.ndarray):
+    """x as the unevaluated sum of two binary16 numbers: hi = fp16(x), lo = fp16(x - hi), the
+    difference taken in fp32 (it is exact there).  Returns (hi, lo) as float32 arrays."""
+    x = np.asarray(x, dtype=np.float32)
+    hi = round_fp16(x)
+    lo = round_fp16(x - hi)
+    return hi, lo
+
+
+def nearest_split(a: np.ndarray, b: np.ndarray):
+    """``nearest`` for the two-term fp16 representation of fp32 descriptors (the extension of the
+    paper's HybridCast, section 3.4.4, that keeps fp32-grade scores on 16-bit matrix hardware):
+
+        score(a, b) = sum_k a_hi[k] b_hi[k] + sum_k a_hi[k] b_lo[k] + sum_k a_lo[k] b_hi[k]
+
+    every product exact (two 11-bit significands), accumulated in fp32 in the order written, k
+    ascending within each sum; the lo*lo term (below 2^-22 of the score) is dropped by definition.
+    Returns (idx, best, second) like ``nearest``.
+    """
+    a_hi, a_lo = split_fp16(a)
+    b_hi, b_lo = split_fp16(b)
+    wide_a = np.concatenate([a_hi, a_hi, a_lo], axis=1)
+    wide_b = np.concatenate([b_hi, b_lo, b_hi], axis=1)
+    return nearest(wide_a, wide_b)
+
+
 def _search(a, b, metric):
-    """(idx, best, second) with "larger is better" scores: the dot product, or minus the squared distance."""
+    """(idx, best, second) with "larger is better" scores: the dot product (plain, or of the two-term
+    fp16 representation), or minus the squared distance."""
     if metric == "dot":
         return nearest(a, b)
+    if metric == "split":
+        return nearest_split(a, b)
     if metric == "l2":
         idx, best, second = nearest_l2(a, b)
         return idx, -best, -second
@@ -178,7 +207,7 @@ def pairs_to_pixels(pairs: np.ndarray, width1: int, width2: int, n: int, m: int,
 
 
 def mutual_dense(d1: np.ndarray, d2: np.ndarray, metric: str = "dot"):
-    """All-pairs mutual nearest neighbours (``metric`` "dot": scores are dot products; "l2": scores
+    """All-pairs mutual nearest neighbours (``metric`` "dot": scores are dot products; "split": dot products of the two-term fp16 representation; "l2": scores
     are minus the squared distance).
 
     Returns a dict with nn12/s12/gap12 (best candidate in d2 for every row of d1),

@@ -540,3 +540,72 @@ def test_pairs_to_pixels_round_trip_and_monotone_filter():
     kept = oracle.pairs_to_pixels(pairs, w1, w2, w1 * h1, w2 * h2, conf1, conf2, 0.3, 0.3).tolist()
     it = iter(xy.tolist())
     assert all(any(row == other for other in it) for row in kept)
+
+
+# ---------------------------------------------------- two-term fp16 representation ("split")
+def test_split_fp16_reconstructs_fp32_values():
+    rng = np.random.default_rng(70)
+    x = np.concatenate([rng.standard_normal(5000), rng.standard_normal(5000) * 1e-3, [0.0, 1.0, -2.5, 65504.0]]).astype(np.float32)
+    hi, lo = oracle.split_fp16(x)
+    # both halves are binary16 numbers
+    assert np.array_equal(hi.astype(np.float16).astype(np.float32), hi)
+    assert np.array_equal(lo.astype(np.float16).astype(np.float32), lo)
+    # hi is the nearest binary16 number; what is left after lo is below 2^-22 |x| (or below the
+    # binary16 subnormal spacing 2^-24, whichever is larger)
+    assert np.all(np.abs(x - hi) <= np.abs(x) * 2.0 ** -11 + 2.0 ** -25)
+    err = np.abs(x.astype(np.float64) - hi.astype(np.float64) - lo.astype(np.float64))
+    assert np.all(err <= np.maximum(np.abs(x) * 2.0 ** -22, 2.0 ** -25))
+    # an fp16-representable value has no second term
+    exact = (rng.integers(-2048, 2049, size=1000) / 256).astype(np.float32)
+    hi, lo = oracle.split_fp16(exact)
+    assert np.array_equal(hi, exact) and not lo.any()
+
+
+def test_nearest_split_scores_are_fp32_grade():
+    rng = np.random.default_rng(71)
+    a, b = unit_rows(rng, 300, 24), unit_rows(rng, 2000, 24)
+    idx, best, second = oracle.nearest_split(a, b)
+    ref_idx, ref_best, ref_second = first_argmax_f64(a, b)          # exact scores of the fp32 inputs
+    # dropped lo*lo term and representation error: < 4 * 2^-22 * sum|a_k b_k| <= 1e-6 for unit rows;
+    # fp32 accumulation of 72 terms adds a few 2^-24.  A dropped cross term would show as ~1e-4.
+    assert np.abs(best - ref_best).max() < 1.5e-6
+    clear = (ref_best - ref_second) > 1e-5
+    assert clear.mean() > 0.99
+    assert np.array_equal(idx[clear], ref_idx[clear])
+    # plain fp16 rounding of the same inputs is two orders of magnitude coarser
+    _, half_best, _ = oracle.nearest(oracle.round_fp16(a), oracle.round_fp16(b))
+    assert np.abs(half_best - ref_best).max() > 5e-5
+
+
+def test_nearest_split_equals_nearest_on_fp16_representable_maps():
+    rng = np.random.default_rng(72)
+    a = (rng.integers(-8, 9, size=(100, 24)) / 8).astype(np.float32)
+    b = (rng.integers(-8, 9, size=(700, 24)) / 8).astype(np.float32)
+    for got, want in zip(oracle.nearest_split(a, b), oracle.nearest(a, b)):
+        assert np.array_equal(got, want)
+
+
+def test_nearest_split_worked_example():
+    # binary16 has 10 fraction bits, so 1 + 2^-12 and 1 + 2^-13 both round to 1:
+    #   a  = (1 + 2^-12, 1)        hi = (1, 1), lo = (2^-12, 0)
+    #   b0 = (0, 1 + 2^-13)        hi = (0, 1), lo = (0, 2^-13)     exact score 1 + 2^-13
+    #   b1 = (1, 0)                hi = (1, 0), lo = (0, 0)         exact score 1 + 2^-12  <- the winner
+    # split scores: b0: hi.hi = 1, hi.lo = 2^-13, lo.hi = 0;  b1: hi.hi = 1, hi.lo = 0, lo.hi = 2^-12.
+    a = np.array([[1.0 + 2.0 ** -12, 1.0]], dtype=np.float32)
+    b = np.array([[0.0, 1.0 + 2.0 ** -13], [1.0, 0.0]], dtype=np.float32)
+    idx, best, second = oracle.nearest_split(a, b)
+    assert idx[0] == 1 and best[0] == np.float32(1.0 + 2.0 ** -12) and second[0] == np.float32(1.0 + 2.0 ** -13)
+    # rounded to fp16 the two candidates tie at 1 and the lower index wins: the wrong one
+    hidx, hbest, hsecond = oracle.nearest(oracle.round_fp16(a), oracle.round_fp16(b))
+    assert hidx[0] == 0 and hbest[0] == 1.0 and hsecond[0] == 1.0
+
+
+def test_split_matching_equals_fp32_matching_where_gaps_are_clear():
+    rng = np.random.default_rng(73)
+    a, b = unit_rows(rng, 1200, 24), unit_rows(rng, 1200, 24)
+    ds = oracle.mutual_dense(a, b, metric="split")
+    dd = oracle.mutual_dense(a, b)
+    clear12, clear21 = dd["gap12"] > 1e-5, dd["gap21"] > 1e-5
+    assert np.array_equal(ds["nn12"][clear12], dd["nn12"][clear12])
+    assert np.array_equal(ds["nn21"][clear21], dd["nn21"][clear21])
+    assert np.abs(ds["s12"] - dd["s12"]).max() < 2e-6
