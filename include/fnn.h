@@ -117,6 +117,21 @@ typedef struct {
  * workspace with fnn_workspace_bytes_opts.  May be combined with FNN_FLAG_NORMALIZE.
  */
 #define FNN_FLAG_L2 4
+/*
+ * FNN_FLAG_SPLIT (fnn_nearest, fnn_reciprocal, fnn_mutual_dense; compute must be FNN_F16, not
+ * combinable with FNN_FLAG_L2, else FNN_E_UNSUPPORTED): fp32-grade scores from the 16-bit
+ * matrix instructions, the precision end of the HybridCast trade-off (section 3.4.4).  Every
+ * descriptor value x (after FNN_FLAG_NORMALIZE, if set) is held as two binary16 numbers,
+ * hi = fp16(x) and lo = fp16(x - hi) (round to nearest even; the difference is exact in
+ * fp32), and
+ *   score(a, b) = sum_k ( a_hi[k] b_hi[k] + a_hi[k] b_lo[k] + a_lo[k] b_hi[k] )
+ * with exact products and fp32 accumulation in unspecified order; the lo*lo term, below
+ * 2^-22 of the score, is left out.  The prepared rows carry 3*d channels (image 1:
+ * [hi, hi, lo], image 2: [hi, lo, hi]) padded to a multiple of 16, so a search costs three
+ * times the matrix work of FNN_F16 and still less than FNN_F32; size the workspace with
+ * fnn_workspace_bytes_opts.  |x| must stay below 65504.
+ */
+#define FNN_FLAG_SPLIT 8
 
 typedef struct {
     int32_t compute;      /* fnn_dtype the products are formed in (see above) */
@@ -135,7 +150,7 @@ const char* fnn_status_string(int32_t status);
  */
 size_t fnn_workspace_bytes(int32_t batch, int64_t n, int64_t m, int32_t d, int64_t n_queries, int32_t compute);
 /*
- * The same for a call that will be made with `opts` (FNN_FLAG_L2 widens the prepared rows);
+ * The same for a call that will be made with `opts` (FNN_FLAG_L2 and FNN_FLAG_SPLIT widen the prepared rows);
  * fnn_workspace_bytes is this function with no flag set.  Returns 0 for invalid shapes or options.
  */
 size_t fnn_workspace_bytes_opts(int32_t batch, int64_t n, int64_t m, int32_t d, int64_t n_queries,

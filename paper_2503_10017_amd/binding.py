@@ -122,14 +122,15 @@ def _map_array(views):
 FNN_FLAG_NORMALIZE = 1
 FNN_FLAG_HALF_ACCUMULATE = 2
 FNN_FLAG_L2 = 4
+FNN_FLAG_SPLIT = 8
 
 
-def _opts(compute, max_iter=0, normalize=False, half_accumulate=False, l2=False):
+def _opts(compute, max_iter=0, normalize=False, half_accumulate=False, l2=False, split=False):
     o = _Opts()
     o.compute = _COMPUTE[compute]
     o.max_iter = int(max_iter)
     o.flags = ((FNN_FLAG_NORMALIZE if normalize else 0) | (FNN_FLAG_HALF_ACCUMULATE if half_accumulate else 0) |
-               (FNN_FLAG_L2 if l2 else 0))
+               (FNN_FLAG_L2 if l2 else 0) | (FNN_FLAG_SPLIT if split else 0))
     return o
 
 
@@ -148,9 +149,9 @@ def fnn_workspace_bytes(batch: int, n: int, m: int, d: int, n_queries: int, comp
 
 
 def fnn_workspace_bytes_opts(batch: int, n: int, m: int, d: int, n_queries: int, compute, max_iter: int = 0,
-                             normalize: bool = False, l2: bool = False) -> int:
+                             normalize: bool = False, l2: bool = False, split: bool = False) -> int:
     """Workspace for a call made with these options (0 when shape or options are invalid)."""
-    o = _opts(compute, max_iter, normalize, l2=l2)
+    o = _opts(compute, max_iter, normalize, l2=l2, split=split)
     return int(load_library().fnn_workspace_bytes_opts(batch, n, m, d, n_queries, ctypes.byref(o)))
 
 
@@ -163,10 +164,11 @@ def _workspace(workspace, need, device):
 def fnn_nearest(src: MapsLike, tgt: MapsLike, q_idx: Optional[torch.Tensor] = None,
                 nq: Optional[int] = None, nq_active: Optional[torch.Tensor] = None, compute="f16",
                 out_idx: Optional[torch.Tensor] = None, out_score: Optional[torch.Tensor] = None,
-                want_score: bool = True, normalize: bool = False, l2: bool = False,
+                want_score: bool = True, normalize: bool = False, l2: bool = False, split: bool = False,
                 workspace: Optional[torch.Tensor] = None, stream=None):
     """One-directional search; returns (out_idx int32[batch][nq], out_score float32[batch][nq] or None).
-    ``l2`` sets FNN_FLAG_L2 (scores are then -1/2 of the squared distance)."""
+    ``l2`` sets FNN_FLAG_L2 (scores are then -1/2 of the squared distance), ``split`` FNN_FLAG_SPLIT
+    (two-term fp16 representation of fp32 descriptors, compute "f16" only)."""
     lib = load_library()
     sv, tv = _as_pairs(src), _as_pairs(tgt)
     batch = len(sv)
@@ -177,8 +179,8 @@ def fnn_nearest(src: MapsLike, tgt: MapsLike, q_idx: Optional[torch.Tensor] = No
         out_idx = torch.empty((batch, nq), dtype=torch.int32, device=device)
     if out_score is None and want_score:
         out_score = torch.empty((batch, nq), dtype=torch.float32, device=device)
-    o = _opts(compute, normalize=normalize, l2=l2)
-    need = fnn_workspace_bytes_opts(batch, sv[0].shape[0], tv[0].shape[0], sv[0].shape[1], nq, compute, l2=l2)
+    o = _opts(compute, normalize=normalize, l2=l2, split=split)
+    need = fnn_workspace_bytes_opts(batch, sv[0].shape[0], tv[0].shape[0], sv[0].shape[1], nq, compute, l2=l2, split=split)
     workspace = _workspace(workspace, need, device)
     sa, ta = _map_array(sv), _map_array(tv)
     st = lib.fnn_nearest(batch, ctypes.cast(sa, ctypes.c_void_p), _ptr(q_idx), nq, _ptr(nq_active),
@@ -190,7 +192,7 @@ def fnn_nearest(src: MapsLike, tgt: MapsLike, q_idx: Optional[torch.Tensor] = No
 
 
 def fnn_reciprocal(d1: MapsLike, d2: MapsLike, seeds: torch.Tensor, max_iter: int = 10, compute="f16",
-                   out: Optional[dict] = None, normalize: bool = False, l2: bool = False,
+                   out: Optional[dict] = None, normalize: bool = False, l2: bool = False, split: bool = False,
                    workspace: Optional[torch.Tensor] = None, stream=None):
     """The FastNN iteration; returns a dict of device tensors
     seed_i, seed_j, seed_iter [batch][n_seeds], pairs [batch][n_seeds][2], n_pairs [batch]."""
@@ -207,8 +209,8 @@ def fnn_reciprocal(d1: MapsLike, d2: MapsLike, seeds: torch.Tensor, max_iter: in
             "pairs": torch.empty((batch, n_seeds, 2), dtype=torch.int32, device=device),
             "n_pairs": torch.empty((batch,), dtype=torch.int32, device=device),
         }
-    o = _opts(compute, max_iter, normalize, l2=l2)
-    need = fnn_workspace_bytes_opts(batch, v1[0].shape[0], v2[0].shape[0], v1[0].shape[1], n_seeds, compute, l2=l2)
+    o = _opts(compute, max_iter, normalize, l2=l2, split=split)
+    need = fnn_workspace_bytes_opts(batch, v1[0].shape[0], v2[0].shape[0], v1[0].shape[1], n_seeds, compute, l2=l2, split=split)
     workspace = _workspace(workspace, need, device)
     a1, a2 = _map_array(v1), _map_array(v2)
     st = lib.fnn_reciprocal(batch, ctypes.cast(a1, ctypes.c_void_p), ctypes.cast(a2, ctypes.c_void_p),
@@ -222,7 +224,7 @@ def fnn_reciprocal(d1: MapsLike, d2: MapsLike, seeds: torch.Tensor, max_iter: in
 
 
 def fnn_mutual_dense(d1: MapsLike, d2: MapsLike, compute="f16", out: Optional[dict] = None,
-                     normalize: bool = False, l2: bool = False, workspace: Optional[torch.Tensor] = None,
+                     normalize: bool = False, l2: bool = False, split: bool = False, workspace: Optional[torch.Tensor] = None,
                      stream=None):
     """All-pairs mutual nearest neighbours; returns a dict of device tensors
     nn12, s12 [batch][n], nn21, s21 [batch][m], pairs [batch][min(n,m)][2], n_pairs [batch]."""
@@ -240,8 +242,8 @@ def fnn_mutual_dense(d1: MapsLike, d2: MapsLike, compute="f16", out: Optional[di
             "pairs": torch.empty((batch, min(n, m), 2), dtype=torch.int32, device=device),
             "n_pairs": torch.empty((batch,), dtype=torch.int32, device=device),
         }
-    o = _opts(compute, normalize=normalize, l2=l2)
-    need = fnn_workspace_bytes_opts(batch, n, m, v1[0].shape[1], 0, compute, l2=l2)
+    o = _opts(compute, normalize=normalize, l2=l2, split=split)
+    need = fnn_workspace_bytes_opts(batch, n, m, v1[0].shape[1], 0, compute, l2=l2, split=split)
     workspace = _workspace(workspace, need, device)
     a1, a2 = _map_array(v1), _map_array(v2)
     st = lib.fnn_mutual_dense(batch, ctypes.cast(a1, ctypes.c_void_p), ctypes.cast(a2, ctypes.c_void_p),

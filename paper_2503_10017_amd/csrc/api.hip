@@ -144,7 +144,7 @@ int32_t check_opts(const fnn_opts* o) {
     if (!o) return FNN_E_NULL;
     if (!valid_dtype(o->compute)) return FNN_E_DTYPE;
     if (o->max_iter < 0) return FNN_E_RANGE;
-    if (o->flags & ~(FNN_FLAG_NORMALIZE | FNN_FLAG_HALF_ACCUMULATE | FNN_FLAG_L2)) return FNN_E_RANGE;
+    if (o->flags & ~(FNN_FLAG_NORMALIZE | FNN_FLAG_HALF_ACCUMULATE | FNN_FLAG_L2 | FNN_FLAG_SPLIT)) return FNN_E_RANGE;
     for (int i = 0; i < 5; ++i)
         if (o->reserved[i] != 0) return FNN_E_RANGE;
     return FNN_OK;
@@ -153,8 +153,13 @@ int32_t check_opts(const fnn_opts* o) {
 // Channels the prepared rows must hold for this call (descriptor + L2 norm channels), or
 // -1 when they do not fit the widest row the kernels take.
 int32_t row_channels(int32_t d, const fnn_opts* o) {
-    const int32_t de = effective_d(d, o->compute, (o->flags & FNN_FLAG_L2) != 0);
-    return de <= FNN_MAX_D ? de : -1;
+    const bool split = (o->flags & FNN_FLAG_SPLIT) != 0;
+    const int32_t de = effective_d(d, o->compute, (o->flags & FNN_FLAG_L2) != 0, split);
+    return de <= (split ? MAX_ROW_CHANNELS : FNN_MAX_D) ? de : -1;
+}
+// FNN_FLAG_SPLIT is defined for fp16 products and the dot-product score only.
+bool split_unsupported(const fnn_opts* o) {
+    return (o->flags & FNN_FLAG_SPLIT) && (o->compute != FNN_F16 || (o->flags & FNN_FLAG_L2));
 }
 
 int32_t check_workspace(const void* ws, size_t have, size_t need) {
@@ -221,6 +226,7 @@ hipError_t prep_both(int32_t batch, const fnn_map* a, const fnn_map* b, const Ma
     pa.compute = compute;
     pa.normalize = (opts->flags & FNN_FLAG_NORMALIZE) ? 1 : 0;
     pa.l2 = (opts->flags & FNN_FLAG_L2) ? 1 : 0;
+    pa.split = (opts->flags & FNN_FLAG_SPLIT) ? 1 : 0;
     return launch_prep(pa, s);
 }
 
@@ -250,7 +256,7 @@ const char* fnn_status_string(int32_t status) {
 
 size_t fnn_workspace_bytes_opts(int32_t batch, int64_t n, int64_t m, int32_t d, int64_t n_queries,
                                 const fnn_opts* opts) {
-    if (!shape_ok(batch, n, m, d, n_queries) || check_opts(opts) != FNN_OK) return 0;
+    if (!shape_ok(batch, n, m, d, n_queries) || check_opts(opts) != FNN_OK || split_unsupported(opts)) return 0;
     const int32_t de = row_channels(d, opts);
     if (de < 0) return 0;
     const int32_t compute = opts->compute;
@@ -290,7 +296,7 @@ int32_t fnn_nearest(int32_t batch, const fnn_map* src, const int32_t* q_idx, int
     if (st != FNN_OK) return st;
     st = check_opts(opts);
     if (st != FNN_OK) return st;
-    if (opts->flags & FNN_FLAG_HALF_ACCUMULATE) return FNN_E_UNSUPPORTED;
+    if ((opts->flags & FNN_FLAG_HALF_ACCUMULATE) || split_unsupported(opts)) return FNN_E_UNSUPPORTED;
     const int64_t n = src[0].n, m = tgt[0].n;
     const int32_t d = src[0].d;
     if (tgt[0].d != d || nq < 0 || nq > MAX_PIXELS) return FNN_E_SHAPE;
@@ -354,7 +360,7 @@ int32_t fnn_nearest_blocked(const fnn_map* src, const int32_t* q_idx, int64_t nq
     st = check_opts(opts);
     if (st != FNN_OK) return st;
     if ((opts->flags & FNN_FLAG_HALF_ACCUMULATE) && opts->compute != FNN_F16) return FNN_E_UNSUPPORTED;
-    if (opts->flags & FNN_FLAG_L2) return FNN_E_UNSUPPORTED;
+    if (opts->flags & (FNN_FLAG_L2 | FNN_FLAG_SPLIT)) return FNN_E_UNSUPPORTED;
     const int64_t n = src[0].n, m = tgt[0].n;
     const int32_t d = src[0].d;
     if (tgt[0].d != d || nq < 0 || nq > MAX_PIXELS || block_rows < 1 || block_cols < 0) return FNN_E_SHAPE;
@@ -404,7 +410,7 @@ int32_t fnn_reciprocal(int32_t batch, const fnn_map* d1, const fnn_map* d2, cons
     if (st != FNN_OK) return st;
     st = check_opts(opts);
     if (st != FNN_OK) return st;
-    if (opts->flags & FNN_FLAG_HALF_ACCUMULATE) return FNN_E_UNSUPPORTED;
+    if ((opts->flags & FNN_FLAG_HALF_ACCUMULATE) || split_unsupported(opts)) return FNN_E_UNSUPPORTED;
     const int64_t n = d1[0].n, m = d2[0].n;
     const int32_t d = d1[0].d;
     if (d2[0].d != d || n_seeds < 0 || n_seeds > MAX_PIXELS) return FNN_E_SHAPE;
@@ -505,7 +511,7 @@ int32_t fnn_mutual_dense(int32_t batch, const fnn_map* d1, const fnn_map* d2, co
     if (st != FNN_OK) return st;
     st = check_opts(opts);
     if (st != FNN_OK) return st;
-    if (opts->flags & FNN_FLAG_HALF_ACCUMULATE) return FNN_E_UNSUPPORTED;
+    if ((opts->flags & FNN_FLAG_HALF_ACCUMULATE) || split_unsupported(opts)) return FNN_E_UNSUPPORTED;
     const int64_t n = d1[0].n, m = d2[0].n;
     const int32_t d = d1[0].d;
     if (d2[0].d != d) return FNN_E_SHAPE;

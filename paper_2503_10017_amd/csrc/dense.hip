@@ -120,8 +120,15 @@ __device__ __forceinline__ void locate_first_lanes(const float (&x)[16], const f
     }
 }
 
+// Rows wider than 64 bytes (fp32 rows of more than 16 channels, the two-term fp16 representation) need more than half the
+// register file for the resident tiles, the query ring and the result buffers: one wave per
+// SIMD there, two otherwise.
 template <int CT, int DP>
-__global__ __launch_bounds__(DENSE_WAVES * 64) __attribute__((amdgpu_waves_per_eu(2)))
+constexpr int dense_waves_per_simd() {
+    return Ops<CT, DP>::ROW_BYTES > 64 ? 1 : 2;
+}
+template <int CT, int DP>
+__global__ __launch_bounds__(DENSE_WAVES * 64) __attribute__((amdgpu_waves_per_eu(dense_waves_per_simd<CT, DP>())))
 void dense_kernel(DenseArgs a) {
     using O = Ops<CT, DP>;
     using Frag = typename O::Frag;
@@ -619,6 +626,10 @@ hipError_t launch_dense(const DenseArgs& a, int batch, int compute, int dp, int3
         if (dp == 16) return launch_dense_t<CT_F16, 16>(a, batch, nn12, s12, nn21, s21, s);
         if (dp == 24) return launch_dense_t<CT_F16, 24>(a, batch, nn12, s12, nn21, s21, s);
         if (dp == 32) return launch_dense_t<CT_F16, 32>(a, batch, nn12, s12, nn21, s21, s);
+        if (dp == 48) return launch_dense_t<CT_F16, 48>(a, batch, nn12, s12, nn21, s21, s);
+        if (dp == 64) return launch_dense_t<CT_F16, 64>(a, batch, nn12, s12, nn21, s21, s);
+        if (dp == 80) return launch_dense_t<CT_F16, 80>(a, batch, nn12, s12, nn21, s21, s);
+        if (dp == 96) return launch_dense_t<CT_F16, 96>(a, batch, nn12, s12, nn21, s21, s);
     } else if (compute == FNN_BF16) {
         if (dp == 16) return launch_dense_t<CT_BF16, 16>(a, batch, nn12, s12, nn21, s21, s);
         if (dp == 24) return launch_dense_t<CT_BF16, 24>(a, batch, nn12, s12, nn21, s21, s);

@@ -13,14 +13,19 @@ typedef unsigned long long u64;
 // Padded channel count of a prepared map: 16-bit formats use one K=16 matrix instruction,
 // a K=16 and a K=8 one (24 channels, no padding for the paper's d = 24) or two K=16 ones;
 // fp32 uses K=2 instructions on channel pairs.
-inline int padded_d(int d, int compute) {
+constexpr int padded_d(int d, int compute) {
     if (compute == FNN_F32) return (d + 7) / 8 * 8;
-    return d <= 16 ? 16 : (d <= 24 ? 24 : 32);
+    return d <= 16 ? 16 : (d <= 24 ? 24 : (d + 15) / 16 * 16);
 }
 // Channels of a prepared row that carry data: the descriptor plus, for the L2 score, the
 // norm terms and their unit partners (two 16-bit halves each, or one fp32 value each).
 inline int l2_extra_channels(int compute) { return compute == FNN_F32 ? 2 : 4; }
-inline int effective_d(int d, int compute, bool l2) { return l2 ? d + l2_extra_channels(compute) : d; }
+// ... or, for the two-term fp16 representation (FNN_FLAG_SPLIT), three copies of the descriptor's
+// channels: [hi, hi, lo] in image 1 and [hi, lo, hi] in image 2.
+inline int effective_d(int d, int compute, bool l2, bool split = false) {
+    return split ? 3 * d : (l2 ? d + l2_extra_channels(compute) : d);
+}
+constexpr int MAX_ROW_CHANNELS = 96;  // widest prepared row (16-bit formats; fp32 rows hold at most 32)
 inline int elem_size(int dtype) { return dtype == FNN_F32 ? 4 : 2; }
 inline int64_t round_up(int64_t x, int64_t a) { return (x + a - 1) / a * a; }
 
@@ -56,6 +61,7 @@ struct PrepArgs {
     int32_t compute;
     int32_t normalize;  // divide every descriptor by its Euclidean norm first (FNN_FLAG_NORMALIZE)
     int32_t l2;         // append the norm channels of the L2 score (FNN_FLAG_L2)
+    int32_t split;      // rows hold the two-term fp16 representation (FNN_FLAG_SPLIT); d is the source's
 };
 hipError_t launch_prep(const PrepArgs& a, hipStream_t s);
 // "no neighbour": idx = -1, score = -inf (score may be NULL)

@@ -94,11 +94,14 @@ __global__ __launch_bounds__(256) void prep_kernel(PrepArgs a) {
         const int64_t row = item / groups;                               // stored row
         const int64_t pix = sd.segment_major ? slot_pixel(row) : row;   // pixel it holds
         const int g = (int)(item % groups);
+        // channels that carry data: the descriptor, or three copies of it (FNN_FLAG_SPLIT)
+        const int data_channels = a.split ? 3 * a.d : a.d;
         float v[8];
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
             const int k = g * 8 + e;
-            v[e] = (pix < sd.n && k < a.d) ? load_as_float(src, pix * sd.row_stride + k, sd.dtype) : 0.0f;
+            const int ch = a.split ? k % a.d : k;
+            v[e] = (pix < sd.n && k < data_channels) ? load_as_float(src, pix * sd.row_stride + ch, sd.dtype) : 0.0f;
         }
         float norm = 0.0f;
         if (a.normalize && pix < sd.n) {
@@ -106,6 +109,21 @@ __global__ __launch_bounds__(256) void prep_kernel(PrepArgs a) {
             if (norm > 0.0f) {
 #pragma unroll
                 for (int e = 0; e < 8; ++e) v[e] = __fdiv_rn(v[e], norm);
+            }
+        }
+        // Two-term fp16 representation: copy 0 holds hi, and of copies 1 and 2 image 1 holds
+        // (hi, lo), image 2 (lo, hi), so that a row of one times a row of the other sums
+        // hi*hi + hi*lo + lo*hi.
+        if (a.split) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const int k = g * 8 + e;
+                if (k < data_channels) {
+                    const int copy = k / a.d;
+                    const float hi = (float)(_Float16)v[e];
+                    const float lo = (float)(_Float16)__fsub_rn(v[e], hi);
+                    v[e] = (copy == 0 || copy == (sd.second_image ? 2 : 1)) ? hi : lo;
+                }
             }
         }
         // L2 score: channels d.. hold the unit partners and -|x|^2/2 (see FNN_FLAG_L2).  For a
@@ -227,6 +245,71 @@ __global__ __launch_bounds__(256) void prep_rows_f32_kernel(PrepArgs a) {
     }
 }
 
+// FNN_FLAG_SPLIT on fp32 sources with d = 8 * IN whole 16-byte vectors: one thread per row
+// reads the descriptor once and writes its three copies (see prep_kernel for the layout).
+template <int IN>
+__global__ __launch_bounds__(256) void prep_split_rows_kernel(PrepArgs a) {
+    prep_side_jobs(a);
+    const int side_idx = blockIdx.y / a.batch;
+    const int b = blockIdx.y % a.batch;
+    const PrepSide& sd = a.side[side_idx];
+    constexpr int D = IN * 8, DP = padded_d(3 * D, FNN_F16);
+    char* dst = reinterpret_cast<char*>(sd.dst) + (int64_t)b * sd.n_pad * DP * 2;
+    const float* src = reinterpret_cast<const float*>(sd.src[b]);
+    const int lo_copy = sd.second_image ? 1 : 2;  // which of copies 1, 2 holds the lo terms
+    for (uint32_t row = blockIdx.x * blockDim.x + threadIdx.x; row < (uint32_t)sd.n_pad; row += gridDim.x * blockDim.x) {
+        const int64_t pix = sd.segment_major ? slot_pixel(row) : (int64_t)row;
+        uint32_t hi[D], lo[D];
+#pragma unroll
+        for (int e = 0; e < D; ++e) hi[e] = lo[e] = 0;
+        if (pix < sd.n) {
+            float v[D];
+            const float4* p = reinterpret_cast<const float4*>(src + pix * sd.row_stride);
+#pragma unroll
+            for (int q = 0; q < IN * 2; ++q) {
+                const float4 x = p[q];
+                v[4 * q + 0] = x.x;
+                v[4 * q + 1] = x.y;
+                v[4 * q + 2] = x.z;
+                v[4 * q + 3] = x.w;
+            }
+            if (a.normalize) {
+                float sum = 0.0f;
+#pragma unroll
+                for (int e = 0; e < D; ++e) sum = __fadd_rn(sum, __fmul_rn(v[e], v[e]));
+                const float norm = __fsqrt_rn(sum);
+                if (norm > 0.0f) {
+#pragma unroll
+                    for (int e = 0; e < D; ++e) v[e] = __fdiv_rn(v[e], norm);
+                }
+            }
+#pragma unroll
+            for (int e = 0; e < D; ++e) {
+                const _Float16 h = (_Float16)v[e];
+                hi[e] = __builtin_bit_cast(uint16_t, h);
+                lo[e] = float_to_f16_rne(__fsub_rn(v[e], (float)h));
+            }
+        }
+        uint4* out = reinterpret_cast<uint4*>(dst + (int64_t)row * DP * 2);
+#pragma unroll
+        for (int q = 0; q < DP / 8; ++q) {
+            uint32_t w[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                uint32_t half[2];
+#pragma unroll
+                for (int t = 0; t < 2; ++t) {
+                    const int k = 8 * q + 2 * e + t;       // compile-time channel of the output row
+                    const int copy = k / D, ch = k % D;
+                    half[t] = (k >= 3 * D) ? 0u : ((copy == lo_copy) ? lo[ch] : hi[ch]);
+                }
+                w[e] = half[0] | (half[1] << 16);
+            }
+            out[q] = make_uint4(w[0], w[1], w[2], w[3]);
+        }
+    }
+}
+
 template <int IN, int OUT>
 static hipError_t launch_prep_rows(const PrepArgs& a, dim3 grid, hipStream_t s) {
     if (a.compute == FNN_F32) return launch(TK_PREP, prep_rows_f32_kernel<IN, OUT, FNN_F32>, grid, dim3(256), 0, s, a);
@@ -325,7 +408,15 @@ hipError_t launch_prep(const PrepArgs& a, hipStream_t s) {
         vector_rows = sd.dtype == FNN_F32 && sd.row_stride % 4 == 0;
         for (int b = 0; b < a.batch && vector_rows; ++b) vector_rows = ((uintptr_t)sd.src[b] % 16) == 0;
     }
-    if (vector_rows && (a.normalize || a.l2) && a.d % 8 == 0) {
+    if (vector_rows && a.split && a.d % 8 == 0 && a.dp == padded_d(3 * a.d, FNN_F16)) {
+        switch (a.d / 8) {
+            case 1: return launch(TK_PREP, prep_split_rows_kernel<1>, grid, dim3(256), 0, s, a);
+            case 2: return launch(TK_PREP, prep_split_rows_kernel<2>, grid, dim3(256), 0, s, a);
+            case 3: return launch(TK_PREP, prep_split_rows_kernel<3>, grid, dim3(256), 0, s, a);
+            case 4: return launch(TK_PREP, prep_split_rows_kernel<4>, grid, dim3(256), 0, s, a);
+        }
+    }
+    if (vector_rows && !a.split && (a.normalize || a.l2) && a.d % 8 == 0) {
         const int in = a.d / 8, out = a.dp / 8;
         if (in == 1 && out == 1) return launch_prep_rows<1, 1>(a, grid, s);
         if (in == 1 && out == 2) return launch_prep_rows<1, 2>(a, grid, s);
@@ -335,7 +426,7 @@ hipError_t launch_prep(const PrepArgs& a, hipStream_t s) {
         if (in == 3 && out == 4) return launch_prep_rows<3, 4>(a, grid, s);
         if (in == 4 && out == 4) return launch_prep_rows<4, 4>(a, grid, s);
     }
-    const bool fast = vector_rows && a.d == a.dp && !a.l2 && !a.normalize;
+    const bool fast = vector_rows && a.d == a.dp && !a.l2 && !a.normalize && !a.split;
     if (fast) {
         switch (a.dp / 8) {
             case 1: return launch_prep_fast<1>(a, grid, s);

@@ -227,6 +227,12 @@ void resolve_kernel(SearchArgs a, int32_t* out_idx, float* out_score) {
 // there is no partial last round and the per-wave start-up cost and the final key merges are
 // paid once per slot.  Two waves per SIMD are what the widest variant fits and what measured
 // best for the narrower ones too, so the widest variant's occupancy sizes every launch.
+// Candidate tiles in flight: rows wider than 128 bytes (the two-term fp16 representation) take
+// a shorter ring so that ring, query fragments and accumulators still fit the register file.
+template <int CT, int DP>
+constexpr int search_ring() {
+    return Ops<CT, DP>::ROW_BYTES > 128 ? 2 : SEARCH_P;
+}
 template <int CT, int DP>
 constexpr int search_g_limit() {
     // a query fragment is ROW_BYTES / 8 registers per lane and G*R of them are resident
@@ -240,7 +246,7 @@ static int search_wgs_per_pair(int batch) {
         int per_cu = 0, dev = 0;
         hipDeviceProp_t prop;
         if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu,
-                                                         search_kernel<CT, DP, SEARCH_R, SEARCH_P, search_g_limit<CT, DP>()>,
+                                                         search_kernel<CT, DP, SEARCH_R, search_ring<CT, DP>(), search_g_limit<CT, DP>()>,
                                                          SEARCH_WAVES * 64, 0) != hipSuccess ||
             hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess)
             return 0;
@@ -268,7 +274,7 @@ static hipError_t launch_search_g(const SearchArgs& a, int batch, hipStream_t s)
                               ((a.m_tiles + SEARCH_MIN_TILES - 1) / SEARCH_MIN_TILES);
     const int64_t need = (max_units + SEARCH_WAVES - 1) / SEARCH_WAVES;
     if (need < wgs) wgs = (int)(need > 0 ? need : 1);
-    return launch(TK_SEARCH, search_kernel<CT, DP, SEARCH_R, SEARCH_P, G>, dim3(wgs, batch), dim3(SEARCH_WAVES * 64), 0, s, a);
+    return launch(TK_SEARCH, search_kernel<CT, DP, SEARCH_R, search_ring<CT, DP>(), G>, dim3(wgs, batch), dim3(SEARCH_WAVES * 64), 0, s, a);
 }
 
 template <int CT, int DP>
@@ -290,6 +296,11 @@ hipError_t launch_search(const SearchArgs& a, int batch, int compute, int dp, hi
         if (dp == 16) return launch_search_t<CT_F16, 16>(a, batch, s);
         if (dp == 24) return launch_search_t<CT_F16, 24>(a, batch, s);
         if (dp == 32) return launch_search_t<CT_F16, 32>(a, batch, s);
+        // rows of the two-term representation (three copies of the channels)
+        if (dp == 48) return launch_search_t<CT_F16, 48>(a, batch, s);
+        if (dp == 64) return launch_search_t<CT_F16, 64>(a, batch, s);
+        if (dp == 80) return launch_search_t<CT_F16, 80>(a, batch, s);
+        if (dp == 96) return launch_search_t<CT_F16, 96>(a, batch, s);
     } else if (compute == FNN_BF16) {
         if (dp == 16) return launch_search_t<CT_BF16, 16>(a, batch, s);
         if (dp == 24) return launch_search_t<CT_BF16, 24>(a, batch, s);
@@ -318,6 +329,10 @@ hipError_t launch_resolve(const SearchArgs& a, int batch, int compute, int dp, i
         if (dp == 16) return launch_resolve_t<CT_F16, 16>(a, batch, out_idx, out_score, s);
         if (dp == 24) return launch_resolve_t<CT_F16, 24>(a, batch, out_idx, out_score, s);
         if (dp == 32) return launch_resolve_t<CT_F16, 32>(a, batch, out_idx, out_score, s);
+        if (dp == 48) return launch_resolve_t<CT_F16, 48>(a, batch, out_idx, out_score, s);
+        if (dp == 64) return launch_resolve_t<CT_F16, 64>(a, batch, out_idx, out_score, s);
+        if (dp == 80) return launch_resolve_t<CT_F16, 80>(a, batch, out_idx, out_score, s);
+        if (dp == 96) return launch_resolve_t<CT_F16, 96>(a, batch, out_idx, out_score, s);
     } else if (compute == FNN_BF16) {
         if (dp == 16) return launch_resolve_t<CT_BF16, 16>(a, batch, out_idx, out_score, s);
         if (dp == 24) return launch_resolve_t<CT_BF16, 24>(a, batch, out_idx, out_score, s);

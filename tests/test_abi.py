@@ -60,6 +60,11 @@ def test_workspace_bytes(lib):
     assert fnn.fnn_workspace_bytes_opts(1, 64, 64, 29, 8, "f16", l2=True) == 0      # 29 + 4 channels do not fit
     assert fnn.fnn_workspace_bytes_opts(1, 64, 64, 12, 8, "f16", l2=True) == fnn.fnn_workspace_bytes_opts(1, 64, 64, 16, 8, "f16")
     assert fnn.fnn_workspace_bytes_opts(1, 64, 64, 24, 8, "f16", max_iter=-1) == 0  # invalid options
+    # two-term representation: 3 * 24 channels padded to 80 instead of 24; every d up to 32 fits; fp16 products only
+    assert fnn.fnn_workspace_bytes_opts(1, 196608, 196608, 24, 3072, "f16", split=True) >= big + 2 * 196608 * (80 - 24) * 2
+    assert fnn.fnn_workspace_bytes_opts(1, 64, 64, 32, 8, "f16", split=True) > 0
+    assert fnn.fnn_workspace_bytes_opts(1, 64, 64, 24, 8, "bf16", split=True) == 0
+    assert fnn.fnn_workspace_bytes_opts(1, 64, 64, 24, 8, "f16", split=True, l2=True) == 0
 
 
 def _map(n=64, d=24, dtype=0, stride=None, data=0x1000):
@@ -107,7 +112,10 @@ def test_argument_errors_are_caught_on_the_host(lib):
     assert _nearest(lib, ok_map, ok_map, _opts(compute=5)) == 3
     assert _nearest(lib, ok_map, ok_map, _opts(max_iter=-1)) == 4      # FNN_E_RANGE
     assert _nearest(lib, ok_map, ok_map, _opts(reserved0=1)) == 4
-    assert _nearest(lib, ok_map, ok_map, _opts(flags=8)) == 4          # unknown flag
+    assert _nearest(lib, ok_map, ok_map, _opts(flags=16)) == 4         # unknown flag
+    assert _nearest(lib, ok_map, ok_map, _opts(compute=2, flags=8)) == 7   # two-term representation: fp16 products only
+    assert _nearest(lib, ok_map, ok_map, _opts(compute=0, flags=8)) == 7
+    assert _nearest(lib, ok_map, ok_map, _opts(flags=12)) == 7         # ... and not with the squared distance
     assert _nearest(lib, ok_map, ok_map, _opts(flags=2)) == 7          # FNN_E_UNSUPPORTED: fp16 accumulation is blocked-only
     assert _nearest(lib, _map(d=29), _map(d=29), _opts(flags=4)) == 2  # squared distance: 29 + 4 channels do not fit
     assert _nearest(lib, _map(d=31), _map(d=31), _opts(compute=0, flags=4)) == 2
