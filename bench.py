@@ -65,6 +65,8 @@ def main() -> int:
                     help="also time the same batch with the L2 normalisation of raw head outputs fused into the prepare pass")
     ap.add_argument("--l2", action="store_true",
                     help="also time the same batch with the squared-distance dist_func (FNN_FLAG_L2)")
+    ap.add_argument("--split", action="store_true",
+                    help="also time the batch with FNN_FLAG_SPLIT (fp32-grade scores from three fp16 products) and with fp32 products")
     ap.add_argument("--f16-maps", action="store_true",
                     help="also time the batch with the maps already stored in the compute format (read in place, no prepare pass)")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -278,6 +280,32 @@ def main() -> int:
             "note": "same 16 pairs, score = -|a-b|^2/2 through 4 extra channels (rows of 32 instead of 24 channels)",
         }
         del lws
+
+    # ---- optional: the same batch at fp32-grade precision, two ways ---------------------------------
+    if args.split:
+        variants = {}
+        for name, comp, kw in (("split_fp16", "f16", {"split": True}), ("fp32_products", "f32", {})):
+            need = fnn.fnn_workspace_bytes_opts(BATCH, N_PIX, N_PIX, D, n_seeds, comp, **kw)
+            sws = torch.empty(need, dtype=torch.uint8, device=dev)
+            sout = fnn.fnn_reciprocal(d1, d2, seeds, MAX_ITER, comp, workspace=sws, **kw)
+            torch.cuda.synchronize()
+            reps = max(args.steps // 4, 3)
+            t0 = time.perf_counter()
+            for _ in range(reps):
+                fnn.fnn_reciprocal(d1, d2, seeds, MAX_ITER, comp, out=sout, workspace=sws, **kw)
+            torch.cuda.synchronize()
+            v_s = (time.perf_counter() - t0) / reps
+            variants[name] = {"ms_per_step": round(v_s * 1e3, 4), "pairs_per_s": round(BATCH / v_s, 2),
+                              "matches_per_pair": round(float(sout["n_pairs"].float().mean().item()), 1)}
+            if name == "split_fp16":
+                split_out = {k: v.clone() for k, v in sout.items()}
+            else:
+                same = (sout["seed_j"] == split_out["seed_j"]) & (sout["seed_i"] == split_out["seed_i"])
+                variants["seeds_with_the_same_match_in_both"] = round(float(same.float().mean().item()), 5)
+            del sws, sout
+        variants["note"] = ("same 16 pairs; split_fp16 = FNN_FLAG_SPLIT (rows of 80 fp16 channels, 5 K=16 matrix instructions per block), "
+                            "fp32_products = compute f32 (12 K=2 fp32 matrix instructions per block)")
+        result["fp32_grade_variants"] = variants
 
     # ---- optional: single-pair latency (configs[1]) ----------------------------------------------
     if args.latency:

@@ -120,12 +120,13 @@ __device__ __forceinline__ void locate_first_lanes(const float (&x)[16], const f
     }
 }
 
-// Rows wider than 64 bytes (fp32 rows of more than 16 channels, the two-term fp16 representation) need more than half the
+// The 16-bit rows of the two-term representation (96 to 192 bytes) need more than half the
 // register file for the resident tiles, the query ring and the result buffers: one wave per
-// SIMD there, two otherwise.
+// SIMD there.  Everything else runs two (measured: fp16 d = 24 2.4 ms against 3.6 ms with one
+// wave, fp32 d = 24 14.0 against 15.6 ms, although both spill a little outside the hot loop).
 template <int CT, int DP>
 constexpr int dense_waves_per_simd() {
-    return Ops<CT, DP>::ROW_BYTES > 64 ? 1 : 2;
+    return (CT != CT_F32 && Ops<CT, DP>::ROW_BYTES > 64) ? 1 : 2;
 }
 template <int CT, int DP>
 __global__ __launch_bounds__(DENSE_WAVES * 64) __attribute__((amdgpu_waves_per_eu(dense_waves_per_simd<CT, DP>())))
