@@ -24,7 +24,12 @@ constexpr int SEARCH_R = 4;           // 32-query blocks whose products are in f
 // A wave keeps G groups of R query blocks resident (G = 1, 2 or 4, chosen per launch), so every
 // candidate tile it loads meets G*R query blocks.
 constexpr int SEARCH_WIDE_MIN_TILES = 256;  // a wave takes more groups only while its chunk stays at least this long
-constexpr int SEARCH_MIN_TILES = 4;   // shortest chunk worth a wave
+// Shortest chunk worth a wave.  Every chunk ends in 64-bit atomic max operations on the keys of
+// the live queries, and atomics on one address are served one after the other (about 13 ns
+// each here): with few live queries and few pairs, 4-tile chunks and one atomic per wave meant
+// 1536 of them per key and 21-34 us per search of a 512x384 map.  8-tile chunks together with
+// the workgroup-level merge in the kernel take 8-12 us (4 and 16 measured slower).
+constexpr int SEARCH_MIN_TILES = 8;
 constexpr int SEARCH_WAVES = 4;       // waves per workgroup
 constexpr int SEARCH_P = 4;           // candidate tiles in flight per wave
 
@@ -86,6 +91,18 @@ void search_kernel(SearchArgs a) {
     const char* tgt = a.tgt + (int64_t)b * a.tgt_bstride;
     const int64_t qbase = (int64_t)b * a.nq;
     const float ninf = -__builtin_inff();
+
+    // With a single row group every unit of this pair serves the same queries, so the waves of
+    // a workgroup first merge their results in LDS and the workgroup sends one atomic per query
+    // instead of one per wave: atomics on one address are served serially, and with few live
+    // queries that chain is what the search waits for.  (row_groups is the same for the whole
+    // workgroup, so the barriers below are uniform.)
+    __shared__ u64 wg_keys[32 * R * G];
+    const bool combine = row_groups == 1;
+    if (combine) {
+        for (int i = threadIdx.x; i < 32 * R * G; i += SEARCH_WAVES * 64) wg_keys[i] = 0;
+        __syncthreads();
+    }
 
     const int64_t units = (int64_t)row_groups * chunks;
     for (int64_t unit = wave; unit < units; unit += n_waves) {
@@ -165,8 +182,19 @@ void search_kernel(SearchArgs a) {
                     best_tile[g][r] = ot;
                 }
                 const int slot = slot0 + (g * R + r) * 32 + c;
-                if (h == 0 && slot < n_act) atomicMax(&a.out_keys[qbase + slot], pack_key(best[g][r], best_tile[g][r]));
+                if (h == 0 && slot < n_act) {
+                    const u64 key = pack_key(best[g][r], best_tile[g][r]);
+                    if (combine) atomicMax(&wg_keys[slot], key);  // slot0 == 0 here: slot < 32 * R * G
+                    else atomicMax(&a.out_keys[qbase + slot], key);
+                }
             }
+    }
+    if (combine) {
+        __syncthreads();
+        for (int i = threadIdx.x; i < min(n_act, 32 * R * G); i += SEARCH_WAVES * 64) {
+            const u64 key = wg_keys[i];
+            if (key != 0) atomicMax(&a.out_keys[qbase + i], key);
+        }
     }
 }
 
