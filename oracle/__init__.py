@@ -15,6 +15,9 @@ What each function follows:
                        (section 3.1.4) L2-normalised per pixel, in fp32.
 * ``nearest_l2``    -- the same search with dist_func = squared Euclidean distance (the other
                        reading of the undefined dist_func; differs on maps that are not unit-norm).
+* ``nearest_split`` -- the same search on the two-term fp16 representation of fp32 descriptors
+                       (hi*hi + hi*lo + lo*hi, fp32 sums): the precise end of HybridCast's
+                       trade-off (section 3.4.4).
 * ``pairs_to_pixels`` -- the step after the path: matches as (w, h) pixel coordinates (section 3.1),
                        thinned by the confidence maps of section 3.1.3.
 * ``nearest_half_accumulate`` -- the "naive FP16 only" negative control of section 3.4.4.
@@ -23,7 +26,7 @@ What each function follows:
                        U^{t+1} = NN_1(V^t), matches M_t are the seeds with
                        U^{t+1} = U^t, converged seeds leave, M is the union of the M_t.
 
-Readings where the paper is silent (all also listed in the design doc): dist_func is the
+Readings where the paper is silent: dist_func is the
 negated dot product; ties go to the lowest index; a seed n with U^{t+1}[n] == U^t[n]
 contributes the pair (U^t[n], V^t[n]); the loop stops only when every seed has converged
 or after ``max_iter`` iterations; unconverged seeds are reported with iter = -1 and are
