@@ -3,6 +3,8 @@ and rejects bad arguments before touching the device (no GPU needed)."""
 import ctypes
 import os
 import re
+import shutil
+import subprocess
 
 import pytest
 
@@ -181,3 +183,14 @@ def test_pairs_to_pixels_argument_errors(lib):
     assert call(batch=0) == 2 and call(batch=65) == 2
     assert call(w1=0) == 2 and call(w2=-3) == 2 and call(max_pairs=-1) == 2 and call(n=-1) == 2
     assert call(n_pairs=0) == 1 and call(count=0) == 1 and call(pairs=0) == 1 and call(out=0) == 1
+
+
+@pytest.mark.skipif(shutil.which("gcc") is None, reason="needs gcc")
+def test_header_is_plain_c_and_usable_from_a_c_program(tmp_path):
+    here = os.path.dirname(os.path.abspath(__file__))
+    exe = str(tmp_path / "c_abi_check")
+    build = subprocess.run(["gcc", "-std=c99", "-pedantic", "-Wall", "-Wextra", "-Werror", "-I", os.path.join(here, "..", "include"),
+                            os.path.join(here, "c_abi_check.c"), "-o", exe, "-ldl"], capture_output=True, text=True)
+    assert build.returncode == 0, build.stderr
+    run = subprocess.run([exe, binding.load_library()._name], capture_output=True, text=True, timeout=120)
+    assert run.returncode == 0 and "c abi ok" in run.stdout, run.stdout + run.stderr
