@@ -10,6 +10,7 @@
 namespace fnn {
 
 constexpr int STEP_THREADS = 1024;
+constexpr size_t DEDUP_LDS_BYTES = 60 * 1024;  // dynamic LDS a launch may ask for without raising the kernel's limit (64 KB incl. static)
 
 struct StepArgs {
     const int32_t* cur_u;     // U^t per slot
@@ -114,12 +115,22 @@ __device__ __forceinline__ int block_scan_int(int value, int* wave_sums, int& to
 // the i of every converged seed in a bitmap, rank the set bits with a prefix sum of word
 // popcounts, and let every converged seed write its pair at the rank of its i (seeds that
 // share a match write the same value to the same place).
+//
+// LOCAL: bitmap and ranks live in the workgroup's LDS (2 * n_words words, passed as dynamic
+// shared memory) instead of the workspace, which takes the global-memory round trips out of
+// this latency-bound kernel; the launcher uses it whenever the two tables fit.
+template <bool LOCAL>
 __global__ __launch_bounds__(STEP_THREADS) void recip_dedup_kernel(DedupArgs a) {
     __shared__ int wave_sums[17];
+    extern __shared__ uint32_t dedup_tables[];
     const int b = blockIdx.x;
     const int64_t base = (int64_t)b * a.n_seeds;
-    uint32_t* bitmap = a.bitmap + (int64_t)b * a.n_words;
-    int32_t* word_rank = a.word_rank + (int64_t)b * a.n_words;
+    uint32_t* bitmap = LOCAL ? dedup_tables : a.bitmap + (int64_t)b * a.n_words;
+    int32_t* word_rank = LOCAL ? reinterpret_cast<int32_t*>(dedup_tables + a.n_words) : a.word_rank + (int64_t)b * a.n_words;
+    if (LOCAL) {
+        for (int w = threadIdx.x; w < a.n_words; w += STEP_THREADS) bitmap[w] = 0;
+        __syncthreads();
+    }
 
     for (int s = threadIdx.x; s < a.n_seeds; s += STEP_THREADS) {
         if (a.seed_iter[base + s] >= 0) {
@@ -193,7 +204,10 @@ hipError_t launch_recip_dedup(const RecipState& st, int32_t n_seeds, int batch,
     a.word_rank = st.word_rank;
     a.pairs = pairs;
     a.n_pairs = n_pairs;
-    return launch(TK_RECIP_DEDUP, recip_dedup_kernel, dim3(batch), dim3(STEP_THREADS), 0, s, a);
+    const size_t tables = (size_t)st.n_words * 2 * sizeof(uint32_t);
+    if (tables <= DEDUP_LDS_BYTES)
+        return launch(TK_RECIP_DEDUP, recip_dedup_kernel<true>, dim3(batch), dim3(STEP_THREADS), tables, s, a);
+    return launch(TK_RECIP_DEDUP, recip_dedup_kernel<false>, dim3(batch), dim3(STEP_THREADS), 0, s, a);
 }
 
 }  // namespace fnn
