@@ -100,6 +100,29 @@ def test_negative_scores_and_ties_to_lowest_index():
     assert np.all(ri % 40 == 0)
 
 
+def test_subnormal_descriptor_values_are_kept():
+    # entries k * 2^-20, |k| < 64: subnormal as fp16 (below 2^-14), ordinary as bf16 and fp32.  Products
+    # k1 k2 2^-40 and their sums are exact in fp32, so a matrix unit that flushed small inputs to
+    # zero would return all-zero scores and index 0 instead of the oracle's answer.
+    rng = np.random.default_rng(21)
+    a = (rng.integers(-63, 64, size=(70, 24)) * 2.0 ** -20).astype(np.float32)
+    b = (rng.integers(-63, 64, size=(900, 24)) * 2.0 ** -20).astype(np.float32)
+    ri, rb, _ = oracle.nearest(a, b)
+    assert rb.max() < 2.0 ** -23 and rb.min() > 0 and len(set(ri.tolist())) > 20
+    for compute in COMPUTES:
+        gi, gs = fnn.fnn_nearest(dev(a), dev(b), compute=compute)
+        torch.cuda.synchronize()
+        assert np.array_equal(host(gi)[0], ri) and np.array_equal(host(gs)[0], rb), compute
+    # small queries against ordinary candidates (scores around 2^-17)
+    b2 = exact_maps(22, 1, 900, 24)[1]
+    ri, rb, _ = oracle.nearest(a, b2)
+    gi, gs = fnn.fnn_nearest(dev(a), dev(b2), compute="f16")
+    di = fnn.fnn_mutual_dense(dev(a), dev(b2), compute="f16")
+    torch.cuda.synchronize()
+    assert np.array_equal(host(gi)[0], ri) and np.array_equal(host(gs)[0], rb)
+    assert np.array_equal(host(di["nn12"])[0], ri) and np.array_equal(host(di["s12"])[0], rb)
+
+
 def test_repeated_calls_are_deterministic():
     a, b = unit_maps(11, 2000, 30000, 24)
     ta, tb = dev(a), dev(b)
