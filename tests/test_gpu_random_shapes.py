@@ -1,7 +1,8 @@
 """Seeded sweep over small random shapes and options for all three entry points, on exactly representable
 maps (entries k/8), so every comparison with the oracle is bit for bit: ragged sizes around the tile (32),
-row-group (128) and super-block (4096) boundaries, every compute format, both dist_funcs, d from 1 to 32,
-batches, repeated and unordered query indices."""
+row-group (128) and super-block (4096) boundaries, every compute format, both dist_funcs, the two-term fp16
+representation (whose second term is zero on these maps, so it must agree with the plain oracle while running
+the wide-row kernels), d from 1 to 32, batches, repeated and unordered query indices."""
 import numpy as np
 import pytest
 import torch
@@ -23,6 +24,12 @@ def draw(rng):
     n, m = (int(SIZES[rng.integers(0, len(SIZES))]) for _ in range(2))
     batch = int(rng.integers(1, 4))
     return compute, l2, d, n, m, batch
+
+
+def draw_split(rng):
+    d = int(rng.integers(1, 33))
+    n, m = (int(SIZES[rng.integers(0, len(SIZES))]) for _ in range(2))
+    return d, n, m, int(rng.integers(1, 4))
 
 
 def maps(rng, batch, n, d):
@@ -73,5 +80,33 @@ def test_reciprocal_and_dense_random_case(case):
         ref = oracle.mutual_dense(a[p], b[p], metric=metric)
         assert np.array_equal(dn["nn12"][p], ref["nn12"]) and np.array_equal(dn["nn21"][p], ref["nn21"]), what
         assert np.array_equal(scale * dn["s12"][p], ref["s12"]) and np.array_equal(scale * dn["s21"][p], ref["s21"]), what
+        k = int(dn["n_pairs"][p])
+        assert np.array_equal(dn["pairs"][p, :k], ref["pairs"]) and np.all(dn["pairs"][p, k:] == -1), what
+
+
+@pytest.mark.parametrize("case", range(16))
+def test_two_term_random_case(case):
+    rng = np.random.default_rng(9000 + case)
+    d, n, m, batch = draw_split(rng)
+    a, b = maps(rng, batch, n, d), maps(rng, batch, m, d)
+    ta, tb = [dev(x) for x in a], [dev(x) for x in b]
+    nq = int(rng.integers(1, 2 * n + 2))
+    q = rng.integers(0, n, size=(batch, nq)).astype(np.int32)
+    gi, gs = fnn.fnn_nearest(ta, tb, q_idx=dev(q), compute="f16", split=True)
+    n_seeds = int(rng.integers(1, min(n, 300) + 1))
+    seeds = np.stack([rng.choice(n, n_seeds, replace=False) for _ in range(batch)]).astype(np.int32)
+    out = fnn.fnn_reciprocal(ta, tb, dev(seeds), max_iter=4, compute="f16", split=True)
+    dense = fnn.fnn_mutual_dense(ta, tb, compute="f16", split=True)
+    torch.cuda.synchronize()
+    got = {k: host(v) for k, v in out.items()}
+    dn = {k: host(v) for k, v in dense.items()}
+    for p in range(batch):
+        what = (d, n, m, batch, p)
+        ri, rbest, _ = oracle.nearest(a[p][q[p]], b[p])
+        assert np.array_equal(host(gi)[p], ri) and np.array_equal(host(gs)[p], rbest), what
+        check_reciprocal_exact(got, p, oracle.reciprocal(a[p], b[p], seeds[p], 4))
+        ref = oracle.mutual_dense(a[p], b[p])
+        assert np.array_equal(dn["nn12"][p], ref["nn12"]) and np.array_equal(dn["nn21"][p], ref["nn21"]), what
+        assert np.array_equal(dn["s12"][p], ref["s12"]) and np.array_equal(dn["s21"][p], ref["s21"]), what
         k = int(dn["n_pairs"][p])
         assert np.array_equal(dn["pairs"][p, :k], ref["pairs"]) and np.all(dn["pairs"][p, k:] == -1), what
