@@ -23,7 +23,7 @@ namespace fnn {
 constexpr int SEARCH_R = 4;           // 32-query blocks whose products are in flight together
 // A wave keeps G groups of R query blocks resident (G = 1, 2 or 4, chosen per launch), so every
 // candidate tile it loads meets G*R query blocks.
-constexpr int SEARCH_WIDE_MIN_TILES = 256;  // a wave takes more groups only while its chunk stays at least this long
+constexpr int SEARCH_WIDE_MIN_TILES = 128;  // a wave takes more groups only while its chunk stays at least this long
 // Shortest chunk worth a wave.  Every chunk ends in 64-bit atomic max operations on the keys of
 // the live queries, and atomics on one address are served one after the other (about 13 ns
 // each here): with few live queries and few pairs, 4-tile chunks and one atomic per wave meant
