@@ -116,17 +116,19 @@ __device__ __forceinline__ int block_scan_int(int value, int* wave_sums, int& to
 // popcounts, and let every converged seed write its pair at the rank of its i (seeds that
 // share a match write the same value to the same place).
 //
-// LOCAL: bitmap and ranks live in the workgroup's LDS (2 * n_words words, passed as dynamic
-// shared memory) instead of the workspace, which takes the global-memory round trips out of
-// this latency-bound kernel; the launcher uses it whenever the two tables fit.
-template <bool LOCAL>
+// LOCAL: bitmap and ranks live in the workgroup's LDS (passed as dynamic shared memory: n_words
+// 32-bit words of bitmap, then n_words ranks of type RANK) instead of the workspace, which takes
+// the global-memory round trips out of this latency-bound kernel; the launcher uses it whenever
+// the two tables fit, with 16-bit ranks (at most 65535 seeds) for the larger images.
+template <bool LOCAL, typename RANK>
 __global__ __launch_bounds__(STEP_THREADS) void recip_dedup_kernel(DedupArgs a) {
     __shared__ int wave_sums[17];
     extern __shared__ uint32_t dedup_tables[];
     const int b = blockIdx.x;
     const int64_t base = (int64_t)b * a.n_seeds;
     uint32_t* bitmap = LOCAL ? dedup_tables : a.bitmap + (int64_t)b * a.n_words;
-    int32_t* word_rank = LOCAL ? reinterpret_cast<int32_t*>(dedup_tables + a.n_words) : a.word_rank + (int64_t)b * a.n_words;
+    RANK* word_rank = LOCAL ? reinterpret_cast<RANK*>(dedup_tables + a.n_words)
+                            : reinterpret_cast<RANK*>(a.word_rank + (int64_t)b * a.n_words);
     if (LOCAL) {
         for (int w = threadIdx.x; w < a.n_words; w += STEP_THREADS) bitmap[w] = 0;
         __syncthreads();
@@ -150,7 +152,7 @@ __global__ __launch_bounds__(STEP_THREADS) void recip_dedup_kernel(DedupArgs a) 
     int count;
     int rank = block_scan_int(mine, wave_sums, count);
     for (int w = w0; w < w1; ++w) {
-        word_rank[w] = rank;
+        word_rank[w] = (RANK)rank;
         rank += __popc(__hip_atomic_load(&bitmap[w], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
     }
     __syncthreads();
@@ -159,7 +161,7 @@ __global__ __launch_bounds__(STEP_THREADS) void recip_dedup_kernel(DedupArgs a) 
         if (a.seed_iter[base + s] >= 0) {
             const uint32_t i = (uint32_t)a.seed_i[base + s];
             const uint32_t word = __hip_atomic_load(&bitmap[i >> 5], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            const int pos = __hip_atomic_load(&word_rank[i >> 5], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) +
+            const int pos = (int)__hip_atomic_load(&word_rank[i >> 5], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) +
                             __popc(word & ((1u << (i & 31)) - 1u));
             a.pairs[(base + pos) * 2 + 0] = (int32_t)i;
             a.pairs[(base + pos) * 2 + 1] = a.seed_j[base + s];
@@ -191,6 +193,28 @@ hipError_t launch_recip_step(const RecipState& st, int which, int32_t n_seeds, i
     return launch(TK_RECIP_STEP, recip_step_kernel, dim3(batch), dim3(STEP_THREADS), 0, s, a);
 }
 
+// Dynamic LDS the 16-bit-rank variant of the final sort may use on this device (0: none beyond
+// the default): what the device grants one workgroup, less the kernel's static LDS and some
+// slack, raised once through the kernel's attribute.
+static size_t dedup_large_lds_limit() {
+    static long long limit = -1;
+    if (limit < 0) {
+        int dev = 0, per_block = 0;
+        limit = 0;
+        if (hipGetDevice(&dev) == hipSuccess &&
+            hipDeviceGetAttribute(&per_block, hipDeviceAttributeMaxSharedMemoryPerBlock, dev) == hipSuccess &&
+            per_block > 64 * 1024) {
+            const int grant = per_block - 1024;
+            if (hipFuncSetAttribute(reinterpret_cast<const void*>(recip_dedup_kernel<true, uint16_t>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, grant) == hipSuccess)
+                limit = grant;
+            else
+                (void)hipGetLastError();  // not granted: the workspace variant serves these sizes
+        }
+    }
+    return (size_t)limit;
+}
+
 hipError_t launch_recip_dedup(const RecipState& st, int32_t n_seeds, int batch,
                               const int32_t* seed_i, const int32_t* seed_j, const int32_t* seed_iter,
                               int32_t* pairs, int32_t* n_pairs, hipStream_t s) {
@@ -206,8 +230,12 @@ hipError_t launch_recip_dedup(const RecipState& st, int32_t n_seeds, int batch,
     a.n_pairs = n_pairs;
     const size_t tables = (size_t)st.n_words * 2 * sizeof(uint32_t);
     if (tables <= DEDUP_LDS_BYTES)
-        return launch(TK_RECIP_DEDUP, recip_dedup_kernel<true>, dim3(batch), dim3(STEP_THREADS), tables, s, a);
-    return launch(TK_RECIP_DEDUP, recip_dedup_kernel<false>, dim3(batch), dim3(STEP_THREADS), 0, s, a);
+        return launch(TK_RECIP_DEDUP, recip_dedup_kernel<true, int32_t>, dim3(batch), dim3(STEP_THREADS), tables, s, a);
+    // larger images: 16-bit ranks, and a workgroup may be granted more than the default 64 KB
+    const size_t narrow = (size_t)st.n_words * (sizeof(uint32_t) + sizeof(uint16_t));
+    if (n_seeds <= 65535 && narrow <= dedup_large_lds_limit())
+        return launch(TK_RECIP_DEDUP, recip_dedup_kernel<true, uint16_t>, dim3(batch), dim3(STEP_THREADS), narrow, s, a);
+    return launch(TK_RECIP_DEDUP, recip_dedup_kernel<false, int32_t>, dim3(batch), dim3(STEP_THREADS), 0, s, a);
 }
 
 }  // namespace fnn
