@@ -67,6 +67,8 @@ def main() -> int:
                     help="also time the same batch with the squared-distance dist_func (FNN_FLAG_L2)")
     ap.add_argument("--split", action="store_true",
                     help="also time the batch with FNN_FLAG_SPLIT (fp32-grade scores from three fp16 products) and with fp32 products")
+    ap.add_argument("--no-ceiling", action="store_true",
+                    help="skip the measurement of what the device sustains on the kernels' bare instruction mix (about a second)")
     ap.add_argument("--f16-maps", action="store_true",
                     help="also time the batch with the maps already stored in the compute format (read in place, no prepare pass)")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -307,6 +309,23 @@ def main() -> int:
                             "fp32_products = compute f32 (12 K=2 fp32 matrix instructions per block)")
         result["fp32_grade_variants"] = variants
 
+    # ---- optional: the device's own ceiling for the kernels' instruction mix ------------------------
+    if not args.no_ceiling and compute != "f32":   # the loops use the 16-bit matrix instructions
+        names = {0: "k16", 1: "k16_k8", 2: "k16_k16", 3: "k16_k8_fold8", 4: "k16_k8_max16"}
+        ns = {names[mix]: round(fnn.fnn_measure_ceiling(mix, 65536, scratch=ws), 2) for mix in names}
+        n_simd = torch.cuda.get_device_properties(dev).multi_processor_count * 4
+        def tflops(ns_per_block, channels):                    # algorithmic flops of a 32x32 block with that many channels
+            return round(2.0 * 32 * 32 * channels * n_simd / ns_per_block / 1e3, 1)
+        result["measured_ceilings"] = {
+            "ns_per_32x32_block_per_simd": ns,
+            "tflops": {"k16 (16 channels)": tflops(ns["k16"], 16), "k16_k8 (24 channels)": tflops(ns["k16_k8"], 24),
+                       "k16_k16 (32 channels)": tflops(ns["k16_k16"], 32),
+                       "k16_k8_fold8 (search arithmetic, 24 channels)": tflops(ns["k16_k8_fold8"], 24),
+                       "k16_k8_max16 (dense arithmetic, 24 channels)": tflops(ns["k16_k8_max16"], 24)},
+            "note": "register-only loops of the matrix instructions (and the 3-input maxima) of one score block, two waves per SIMD, "
+                    "all %d SIMDs; the published fp16 peak is 2500 TFLOP/s" % n_simd,
+        }
+
     # ---- optional: single-pair latency (configs[1]) ----------------------------------------------
     if args.latency:
         a, b = synth.config_pair(2)
@@ -447,6 +466,16 @@ def main() -> int:
         }
         del ref
 
+    # the kernels against the device's own ceiling for their arithmetic (measured above, same process)
+    if "measured_ceilings" in result:
+        ceil_tf = result["measured_ceilings"]["tflops"]
+        first = [row for row in result.get("live_searches", []) if row.get("bound") == "mfma"]
+        if first:
+            result["measured_ceilings"]["first_search_fraction_of_search_arithmetic_ceiling"] = round(
+                first[0]["TFLOP/s"] / ceil_tf["k16_k8_fold8 (search arithmetic, 24 channels)"], 3)
+        if "dense_mutual" in result:
+            result["measured_ceilings"]["dense_kernel_fraction_of_dense_arithmetic_ceiling"] = round(
+                result["dense_mutual"]["roofline"]["achieved"] / ceil_tf["k16_k8_max16 (dense arithmetic, 24 channels)"], 3)
     print(json.dumps(result))
     return 0
 

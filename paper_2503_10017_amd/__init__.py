@@ -18,6 +18,7 @@ from .binding import (  # noqa: F401
     fnn_status_string,
     fnn_trace_begin,
     fnn_trace_end,
+    fnn_measure_ceiling,
     fnn_workspace_bytes,
     fnn_workspace_bytes_opts,
     library_path,

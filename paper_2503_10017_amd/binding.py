@@ -76,6 +76,8 @@ def load_library():
     lib.fnn_trace_end.argtypes = [i32, vp, vp, vp]
     lib.fnn_trace_kind_name.restype = ctypes.c_char_p
     lib.fnn_trace_kind_name.argtypes = [i32]
+    lib.fnn_measure_ceiling.restype = i32
+    lib.fnn_measure_ceiling.argtypes = [i32, i32, vp, sz, vp, vp]
     _lib = lib
     return lib
 
@@ -313,3 +315,16 @@ def fnn_trace_end(capacity: int = 4096):
         raise FnnError(st, "fnn_trace_end")
     count = min(int(n.value), capacity)
     return [(lib.fnn_trace_kind_name(kinds[i]).decode(), float(ms[i])) for i in range(count)]
+
+
+def fnn_measure_ceiling(mix: int, blocks_per_wave: int = 65536, scratch: Optional[torch.Tensor] = None, stream=None) -> float:
+    """Nanoseconds per 32x32 score block and SIMD for the bare instruction mix ``mix`` (see fnn.h); waits for the result."""
+    lib = load_library()
+    if scratch is None:
+        scratch = torch.empty(4 << 20, dtype=torch.uint8, device="cuda")
+    ns = ctypes.c_float(0.0)
+    st = lib.fnn_measure_ceiling(mix, blocks_per_wave, _ptr(scratch), scratch.numel() * scratch.element_size(),
+                                 ctypes.byref(ns), _stream_ptr(stream, scratch.device))
+    if st != 0:
+        raise FnnError(st, "fnn_measure_ceiling")
+    return float(ns.value)

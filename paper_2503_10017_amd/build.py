@@ -11,7 +11,7 @@ LIB_DIR = os.path.join(_HERE, "lib")
 LIB_PATH = os.path.join(LIB_DIR, "libfnn.so")
 OBJ_DIR = os.path.join(_HERE, "_build")
 
-SOURCES = ["prep.hip", "search.hip", "recip.hip", "dense.hip", "blocked.hip", "pixels.hip", "api.hip", "trace.hip"]
+SOURCES = ["prep.hip", "search.hip", "recip.hip", "dense.hip", "blocked.hip", "pixels.hip", "api.hip", "trace.hip", "ceiling.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden",
