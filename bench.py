@@ -49,6 +49,19 @@ def searches_from_iters(seed_iter, n_seeds, max_iter):
     return counts
 
 
+def csrc_fingerprint() -> str:
+    """Hash of the kernel sources: ties a stored counter measurement to the code it was taken on."""
+    import hashlib
+    d = os.path.join(ROOT, "paper_2503_10017_amd", "csrc")
+    h = hashlib.sha1()
+    for name in sorted(os.listdir(d)):
+        if name.endswith((".hip", ".hpp")):
+            h.update(name.encode())
+            with open(os.path.join(d, name), "rb") as f:
+                h.update(f.read())
+    return h.hexdigest()[:16]
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -58,7 +71,7 @@ def main() -> int:
     ap.add_argument("--no-dense", action="store_true", help="skip the dense mutual-NN leg")
     ap.add_argument("--no-cfg5", action="store_true", help="skip the 1024x768 bf16 leg (configs[4]: dense mutual NN + reciprocal)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
-    ap.add_argument("--latency", action="store_true", help="also time a single pair (adds search launches)")
+    ap.add_argument("--no-latency", action="store_true", help="skip the single-pair latency leg (configs[1])")
     ap.add_argument("--contrast", action="store_true",
                     help="also time the paper's blocked schedules (Algorithms 1 and 2 with a materialised score block)")
     ap.add_argument("--normalize", action="store_true",
@@ -167,8 +180,13 @@ def main() -> int:
         t_mfma = fl / (peak * 1e12) * 1e6
         t_hbm = by / (PEAK_HBM * 1e9) * 1e6
         per_search_rows.append({
-            "queries": k_act, "us": round(us, 1), "TFLOP/s": round(fl / us / 1e6, 1), "GB/s": round(by / us / 1e3, 1),
+            "queries": k_act, "us": round(us, 1), "bytes": by, "TFLOP/s": round(fl / us / 1e6, 1), "GB/s": round(by / us / 1e3, 1),
             "bound": "mfma" if t_mfma >= t_hbm else "hbm", "frac_of_bound": round(max(t_mfma, t_hbm) / us, 3)})
+
+    hbm_rows = [r for r in per_search_rows if r["bound"] == "hbm"]
+    hbm_bytes = sum(r["bytes"] for r in hbm_rows)
+    hbm_us = sum(r["us"] for r in hbm_rows)
+    hbm_gbs = hbm_bytes / hbm_us / 1e3 if hbm_us > 0 else 0.0
 
     result = {
         "metric": "FastNN image pairs/sec at 512x384 D=24",
@@ -206,6 +224,13 @@ def main() -> int:
             "kernel": "search_kernel", "bound": "hbm", "achieved": round(achieved_gbs, 1), "peak": PEAK_HBM,
             "unit": "GB/s", "frac": round(achieved_gbs / PEAK_HBM, 4), "bytes_per_launch": bytes_per_launch,
         },
+        "roofline_hbm_bound": {
+            "kernel": "search_kernel", "bound": "hbm", "achieved": round(hbm_gbs, 1), "peak": PEAK_HBM, "unit": "GB/s",
+            "frac": round(hbm_gbs / PEAK_HBM, 4), "launches_per_step": len(hbm_rows), "bytes_per_step": hbm_bytes,
+            "us_per_step": round(hbm_us, 1),
+            "note": "sum of algorithmic bytes / sum of durations over the search launches of a step whose bound is HBM "
+                    "(few live queries: streaming the candidate maps takes longer than the matrix work at peak)",
+        },
         "input_generation_s": round(gen_s, 1),
     }
 
@@ -218,6 +243,8 @@ def main() -> int:
         result["roofline"]["traffic"] = traffic.get("search_kernel_bytes_per_launch")
         result["roofline_hbm"]["traffic"] = traffic.get("search_kernel_bytes_per_launch")
         result["roofline"]["traffic_source"] = traffic.get("source")
+        # the counters were read on one revision of the kernels; say so when the sources have changed since
+        result["roofline"]["traffic_stale"] = traffic.get("csrc_fingerprint") != csrc_fingerprint()
     else:
         traffic = {}
 
@@ -311,7 +338,8 @@ def main() -> int:
 
     # ---- optional: the device's own ceiling for the kernels' instruction mix ------------------------
     if not args.no_ceiling and compute != "f32":   # the loops use the 16-bit matrix instructions
-        names = {0: "k16", 1: "k16_k8", 2: "k16_k16", 3: "k16_k8_fold8", 4: "k16_k8_max16"}
+        names = {0: "k16", 1: "k16_k8", 2: "k16_k16", 3: "k16_k8_fold8", 4: "k16_k8_max16", 5: "quad_16x16x32",
+                 6: "bf16_k16_k8", 7: "bf16_k16_k8_fold8", 8: "bf16_k16_k8_max16"}
         ns = {names[mix]: round(fnn.fnn_measure_ceiling(mix, 65536, scratch=ws), 2) for mix in names}
         n_simd = torch.cuda.get_device_properties(dev).multi_processor_count * 4
         def tflops(ns_per_block, channels):                    # algorithmic flops of a 32x32 block with that many channels
@@ -321,13 +349,19 @@ def main() -> int:
             "tflops": {"k16 (16 channels)": tflops(ns["k16"], 16), "k16_k8 (24 channels)": tflops(ns["k16_k8"], 24),
                        "k16_k16 (32 channels)": tflops(ns["k16_k16"], 32),
                        "k16_k8_fold8 (search arithmetic, 24 channels)": tflops(ns["k16_k8_fold8"], 24),
-                       "k16_k8_max16 (dense arithmetic, 24 channels)": tflops(ns["k16_k8_max16"], 24)},
+                       "k16_k8_max16 (dense arithmetic, 24 channels)": tflops(ns["k16_k8_max16"], 24),
+                       "quad_16x16x32 (24 channels padded to 32, four 16x16x32 instructions)": tflops(ns["quad_16x16x32"], 24),
+                       "bf16_k16_k8 (24 channels)": tflops(ns["bf16_k16_k8"], 24),
+                       "bf16_k16_k8_fold8 (search arithmetic, bf16)": tflops(ns["bf16_k16_k8_fold8"], 24),
+                       "bf16_k16_k8_max16 (dense arithmetic, bf16)": tflops(ns["bf16_k16_k8_max16"], 24)},
+            "matrix_only_ceiling_fraction_of_published_peak_d24": round(
+                max(tflops(ns["k16_k8"], 24), tflops(ns["quad_16x16x32"], 24)) / PEAK_MFMA_16BIT, 4),
             "note": "register-only loops of the matrix instructions (and the 3-input maxima) of one score block, two waves per SIMD, "
                     "all %d SIMDs; the published fp16 peak is 2500 TFLOP/s" % n_simd,
         }
 
     # ---- optional: single-pair latency (configs[1]) ----------------------------------------------
-    if args.latency:
+    if not args.no_latency:
         a, b = synth.config_pair(2)
         ta, tb = torch.from_numpy(a).to(dev), torch.from_numpy(b).to(dev)
         ts = seeds[:1].contiguous()
@@ -338,6 +372,8 @@ def main() -> int:
             fnn.fnn_reciprocal(ta, tb, ts, MAX_ITER, compute, out=o1, workspace=ws)
         torch.cuda.synchronize()
         result["single_pair_ms"] = round((time.perf_counter() - t0) / 50 * 1e3, 4)
+        result["single_pair"] = {"workload": "configs[1]: one 512x384 D=24 pair, FastNN reciprocal, 3072 seeds, max_iter 10",
+                                 "ms_per_call": result["single_pair_ms"], "matches": int(o1["n_pairs"][0]), "calls_timed": 50}
 
     # ---- optional: the paper's schedules against the fused search, first search of one pair --------
     if args.contrast:
@@ -476,6 +512,10 @@ def main() -> int:
         if "dense_mutual" in result:
             result["measured_ceilings"]["dense_kernel_fraction_of_dense_arithmetic_ceiling"] = round(
                 result["dense_mutual"]["roofline"]["achieved"] / ceil_tf["k16_k8_max16 (dense arithmetic, 24 channels)"], 3)
+        lp = result.get("large_pair", {})
+        if lp.get("dense_kernel_frac_of_mfma_peak"):
+            result["measured_ceilings"]["large_pair_dense_kernel_fraction_of_bf16_dense_arithmetic_ceiling"] = round(
+                lp["dense_kernel_frac_of_mfma_peak"] * PEAK_MFMA_16BIT / ceil_tf["bf16_k16_k8_max16 (dense arithmetic, bf16)"], 3)
     print(json.dumps(result))
     return 0
 

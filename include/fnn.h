@@ -10,11 +10,11 @@
  *                     Algorithm 3 ("HybridCast", section 3.4.4): descriptors may be rounded
  *                     to a 16-bit format, products are accumulated and the best candidate
  *                     is selected in fp32.
- *   fnn_reciprocal    the FastNN iteration (section 3.2, "FastNN Algorithm", steps 1-4):
+ *   fnn_reciprocal    the FastNN iteration (section 3.2.5, "FastNN Algorithm", steps 1-4):
  *                     seeds in image 1, ping-pong searches, seeds leave when they return to
  *                     where they were, the result is the set of reciprocal matches.
  *   fnn_mutual_dense  the all-pairs mutual nearest neighbours that FastNN approximates
- *                     (section 3.2, "Problem Context").
+ *                     (section 3.2.5, "Problem Context").
  *
  * Conventions shared by every entry point
  * ---------------------------------------
@@ -27,14 +27,19 @@
  *  - `batch` independent image pairs share shapes; maps are passed as HOST arrays of
  *    `batch` fnn_map structs (1 <= batch <= FNN_MAX_BATCH); every other array is ONE
  *    contiguous DEVICE buffer with the batch index outermost.
- *  - The caller owns every buffer.  The library allocates no device memory, keeps no state
- *    between calls (but see fnn_trace_begin) and touches only the outputs and `workspace` (device, >= fnn_workspace_bytes(),
- *    256-byte aligned).  All work is enqueued on `stream` (a hipStream_t, NULL = default
- *    stream) and the call returns without waiting; outputs are valid once the stream has
- *    reached that point.  Two calls that share a workspace must be ordered by the stream.
- *    A call may be captured into a HIP graph (it launches kernels only, clears its buffers with
+ *  - The caller owns every buffer.  The library allocates no device memory and touches only the
+ *    outputs and `workspace` (device, >= fnn_workspace_bytes(), 256-byte aligned).  All work is
+ *    enqueued on `stream` (a hipStream_t, NULL = default stream) and the call returns without
+ *    waiting; outputs are valid once the stream has reached that point.  Two calls that share
+ *    a workspace must be ordered by the stream.
+ *  - State between calls: none that affects results.  The library keeps, per device, a small
+ *    cache of launch shapes (how many workgroups of its kernels the device holds, the LDS a
+ *    workgroup may be granted); it is filled under a lock by the first call on each device, so
+ *    calls from several host threads and on several devices are safe.  The measurement aids of
+ *    fnn_measure.h hold process-wide state of their own and are not thread-safe.
+ *  - A call may be captured into a HIP graph (it launches kernels only, clears its buffers with
  *    kernels and never synchronises) once the same entry point has run eagerly on the device,
- *    which fills the launch-shape caches.
+ *    which fills that cache.
  *  - The maps are read by the enqueued work and never written: keep them alive and unchanged
  *    until the stream has passed the call.  fnn_nearest and fnn_reciprocal copy a map into the
  *    workspace (cast to the compute format, rows padded) unless the caller's array already
@@ -87,7 +92,7 @@ typedef struct {
 } fnn_map;
 
 /*
- * FNN_FLAG_NORMALIZE: the maps are raw matching-head outputs (section 3.1.4, "Matching Head");
+ * FNN_FLAG_NORMALIZE: the maps are raw matching-head outputs (section 3.2.4, "Matching Head");
  * every descriptor is divided by its Euclidean norm before the cast to the compute format:
  * norm2 = sum_k x[k]*x[k] in fp32 (k ascending, products and sums rounded separately),
  * y[k] = x[k] / sqrt(norm2) with correctly rounded fp32 sqrt and division; an all-zero
@@ -96,8 +101,8 @@ typedef struct {
 #define FNN_FLAG_NORMALIZE 1
 /*
  * FNN_FLAG_HALF_ACCUMULATE (fnn_nearest_blocked with compute == FNN_F16 only; the other
- * entry points answer FNN_E_UNSUPPORTED): the negative control of section 3.4.4 ("if one
- * naively uses only FP16 ..."): every product is rounded to fp16 and the sum is accumulated
+ * entry points answer FNN_E_UNSUPPORTED): the negative control for section 3.4.4, which
+ * warns against a plain fp16 computation: every product is rounded to fp16 and the sum is accumulated
  * in fp16, k ascending (IEEE binary16 multiply and add, no fused multiply-add); only the
  * selection stays in fp32.  Exists to measure how many nearest neighbours that changes.
  */
@@ -171,7 +176,7 @@ int32_t fnn_nearest(int32_t batch, const fnn_map* src, const int32_t* q_idx, int
                     void* workspace, size_t workspace_bytes, void* stream);
 
 /*
- * The FastNN iteration (section 3.2).  seeds: device int32[batch][n_seeds], pixel ids of
+ * The FastNN iteration (section 3.2.5, "FastNN Algorithm").  seeds: device int32[batch][n_seeds], pixel ids of
  * d1 (duplicates allowed).  With U^0 = seeds, V^0 = NN_2(U^0), then for t = 0..max_iter-1:
  * U^{t+1} = NN_1(V^t); a seed with U^{t+1} == U^t has converged: it yields the match
  * (U^t, V^t), records iteration t and leaves; the others continue with
@@ -192,7 +197,7 @@ int32_t fnn_reciprocal(int32_t batch, const fnn_map* d1, const fnn_map* d2,
                        void* workspace, size_t workspace_bytes, void* stream);
 
 /*
- * All-pairs mutual nearest neighbours (section 3.2, "Problem Context").  With
+ * All-pairs mutual nearest neighbours (section 3.2.5, "Problem Context").  With
  * S[i][j] = score(d1[i], d2[j]):
  *   nn12[b][i] = lowest j maximising S[i][j],  s12 = that score      (int32/float [batch][n])
  *   nn21[b][j] = lowest i maximising S[i][j],  s21 = that score      (int32/float [batch][m])
@@ -210,7 +215,7 @@ int32_t fnn_mutual_dense(int32_t batch, const fnn_map* d1, const fnn_map* d2, co
 /*
  * The match set in the problem statement's own terms (section 3.1, "Problem Statement": a
  * correspondence is a pair of pixels i = (w_i, h_i), j = (w_j, h_j)), optionally thinned by
- * the confidence maps c1, c2 that the regression heads emit (section 3.1.3).  For pair b and
+ * the confidence maps c1, c2 that the regression heads emit (section 3.2.3).  For pair b and
  * p < min(n_pairs[b], max_pairs), in input order, the match (i, j) = pairs[b][p] is KEPT iff
  *   0 <= i < n, 0 <= j < m,
  *   conf1 == NULL or conf1[b*n + i] >= min_conf1,  conf2 == NULL or conf2[b*m + j] >= min_conf2
@@ -245,38 +250,6 @@ int32_t fnn_nearest_blocked(const fnn_map* src, const int32_t* q_idx, int64_t nq
                             const fnn_opts* opts, int32_t block_rows, int32_t block_cols,
                             int32_t* out_idx, float* out_score,
                             void* workspace, size_t workspace_bytes, void* stream);
-
-/*
- * Measurement aid (not part of the paper's method; used by the benchmark).  Between
- * fnn_trace_begin and fnn_trace_end every kernel the library launches -- up to max_kernels,
- * later ones run untimed -- carries its own pair of HIP events, so that fnn_trace_end can
- * report each kernel's device-side duration.  fnn_trace_end waits for the traced kernels,
- * writes min(*n_recorded, capacity) entries (kinds[i] names the kernel, see
- * fnn_trace_kind_name; milliseconds[i] is its duration, in launch order) to HOST arrays and
- * closes the trace.  This is the only state the library holds; it is process-wide and not
- * thread-safe, and a trace must not be open during HIP graph capture.
- */
-int32_t fnn_trace_begin(int32_t max_kernels);
-int32_t fnn_trace_end(int32_t capacity, int32_t* kinds, float* milliseconds, int32_t* n_recorded);
-const char* fnn_trace_kind_name(int32_t kind);
-
-/*
- * Measurement aid (not part of the paper's method; bench.py --ceiling): the time this device
- * needs per 32x32 block of scores for the bare instruction mix of the kernels, in a loop that
- * touches registers only -- the yardstick the kernels' own times are held against.
- *   mix 0: one K=16 fp16 matrix instruction per block (16 channels)
- *   mix 1: a K=16 and a K=8 instruction (the 24-channel block of the paper's d = 24)
- *   mix 2: two K=16 instructions (a 32-channel block)
- *   mix 3: mix 1 plus the eight 3-input maxima that fold a block (search kernel arithmetic)
- *   mix 4: mix 1 plus sixteen 3-input maxima per block (dense kernel arithmetic)
- * Runs two waves on every SIMD of the current device, each doing blocks_per_wave blocks
- * (>= 4), three times, WAITS for them, and writes the best time as nanoseconds per block and
- * SIMD to *ns_per_block (host).  scratch: device memory, 4-byte aligned, at least
- * 2048 bytes per compute unit (one word per thread is stored there).
- * Errors: FNN_E_NULL, FNN_E_RANGE (mix, blocks_per_wave), FNN_E_WORKSPACE, FNN_E_HIP.
- */
-int32_t fnn_measure_ceiling(int32_t mix, int32_t blocks_per_wave, void* scratch, size_t scratch_bytes,
-                            float* ns_per_block, void* stream);
 
 #ifdef __cplusplus
 }

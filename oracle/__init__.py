@@ -9,19 +9,19 @@ What each function follows:
                        brute force over all candidates, strict improvement, lowest index
                        on ties, score = dot product in fp32 (C, ``fnn_oracle.c``).
 * ``mutual_dense``  -- the "traditional mutual nearest neighbour" definition the paper
-                       contrasts FastNN with (section 3.2, "Problem Context"): a pair
+                       contrasts FastNN with (section 3.2.5, "Problem Context"): a pair
                        (i, j) is kept when j is i's best candidate and i is j's.
 * ``normalize``     -- the producer step in front of the search: the matching head's maps
-                       (section 3.1.4) L2-normalised per pixel, in fp32.
+                       (section 3.2.4) L2-normalised per pixel, in fp32.
 * ``nearest_l2``    -- the same search with dist_func = squared Euclidean distance (the other
                        reading of the undefined dist_func; differs on maps that are not unit-norm).
 * ``nearest_split`` -- the same search on the two-term fp16 representation of fp32 descriptors
                        (hi*hi + hi*lo + lo*hi, fp32 sums): the precise end of HybridCast's
                        trade-off (section 3.4.4).
 * ``pairs_to_pixels`` -- the step after the path: matches as (w, h) pixel coordinates (section 3.1),
-                       thinned by the confidence maps of section 3.1.3.
+                       thinned by the confidence maps of section 3.2.3.
 * ``nearest_half_accumulate`` -- the "naive FP16 only" negative control of section 3.4.4.
-* ``reciprocal``    -- the FastNN iteration (section 3.2, "FastNN Algorithm", steps 1-4),
+* ``reciprocal``    -- the FastNN iteration (section 3.2.5, "FastNN Algorithm", steps 1-4),
                        step by step: U^0 = seeds, V^0 = NN_2(U^0); each iteration
                        U^{t+1} = NN_1(V^t), matches M_t are the seeds with
                        U^{t+1} = U^t, converged seeds leave, M is the union of the M_t.
@@ -195,7 +195,7 @@ def nearest_half_accumulate(a: np.ndarray, b: np.ndarray):
 def pairs_to_pixels(pairs: np.ndarray, width1: int, width2: int, n: int, m: int, conf1=None, conf2=None,
                     min_conf1: float = 0.0, min_conf2: float = 0.0) -> np.ndarray:
     """The matches (flat pixel ids) as the paper's problem statement writes them (section 3.1):
-    i = (w_i, h_i), j = (w_j, h_j), keeping only matches whose confidences (section 3.1.3's maps
+    i = (w_i, h_i), j = (w_j, h_j), keeping only matches whose confidences (section 3.2.3's maps
     c1, c2, when given) reach the thresholds.  One match at a time, in order; int32[P'][4]."""
     rows = []
     for i, j in np.asarray(pairs).reshape(-1, 2).tolist():

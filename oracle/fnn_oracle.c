@@ -95,7 +95,7 @@ void oracle_nearest_l2(const float* a, int64_t k_rows, const float* b, int64_t m
 }
 
 /*
- * The producer step in front of the search (paper section 3.1.4, "Matching Head": the maps
+ * The producer step in front of the search (paper section 3.2.4, "Matching Head": the maps
  * D1, D2 come out of the head un-normalised): every descriptor divided by its Euclidean norm.
  * norm2 = sum_k x[k]*x[k] in fp32, k ascending, every product and every sum rounded on its
  * own; y[k] = x[k] / sqrtf(norm2) (IEEE sqrt and division); an all-zero descriptor stays zero.

@@ -1,7 +1,7 @@
 """ctypes binding of libfnn.so: argument marshalling only.
 
 Every function here has the name and meaning of the C entry point it wraps (see
-include/fnn.h).  torch supplies device memory and the current stream; all arithmetic of
+include/fnn.h, include/fnn_measure.h).  torch supplies device memory and the current stream; all arithmetic of
 the matching path runs inside the library's kernels.
 """
 from __future__ import annotations
@@ -73,7 +73,7 @@ def load_library():
     lib.fnn_trace_begin.restype = i32
     lib.fnn_trace_begin.argtypes = [i32]
     lib.fnn_trace_end.restype = i32
-    lib.fnn_trace_end.argtypes = [i32, vp, vp, vp]
+    lib.fnn_trace_end.argtypes = [i32, vp, vp, vp, vp]
     lib.fnn_trace_kind_name.restype = ctypes.c_char_p
     lib.fnn_trace_kind_name.argtypes = [i32]
     lib.fnn_measure_ceiling.restype = i32
@@ -304,21 +304,25 @@ def fnn_trace_begin(max_kernels: int = 4096) -> None:
         raise FnnError(st, "fnn_trace_begin")
 
 
-def fnn_trace_end(capacity: int = 4096):
-    """Returns a list of (kernel name, milliseconds) in launch order and closes the trace."""
+def fnn_trace_end(capacity: int = 4096, details: bool = False):
+    """Returns a list of (kernel name, milliseconds) in launch order and closes the trace; with
+    ``details`` the entries are (kernel name, milliseconds, detail) -- see include/fnn_measure.h."""
     lib = load_library()
     kinds = (ctypes.c_int32 * capacity)()
     ms = (ctypes.c_float * capacity)()
+    det = (ctypes.c_int32 * capacity)()
     n = ctypes.c_int32(0)
-    st = lib.fnn_trace_end(capacity, kinds, ms, ctypes.byref(n))
+    st = lib.fnn_trace_end(capacity, kinds, ms, det, ctypes.byref(n))
     if st != 0:
         raise FnnError(st, "fnn_trace_end")
     count = min(int(n.value), capacity)
+    if details:
+        return [(lib.fnn_trace_kind_name(kinds[i]).decode(), float(ms[i]), int(det[i])) for i in range(count)]
     return [(lib.fnn_trace_kind_name(kinds[i]).decode(), float(ms[i])) for i in range(count)]
 
 
 def fnn_measure_ceiling(mix: int, blocks_per_wave: int = 65536, scratch: Optional[torch.Tensor] = None, stream=None) -> float:
-    """Nanoseconds per 32x32 score block and SIMD for the bare instruction mix ``mix`` (see fnn.h); waits for the result."""
+    """Nanoseconds per 32x32 score block and SIMD for the bare instruction mix ``mix`` (see fnn_measure.h); waits for the result."""
     lib = load_library()
     if scratch is None:
         scratch = torch.empty(4 << 20, dtype=torch.uint8, device="cuda")

@@ -1,4 +1,4 @@
-// Measurement aid behind fnn_measure_ceiling (see include/fnn.h): what this device sustains on
+// Measurement aid behind fnn_measure_ceiling (see include/fnn_measure.h): what this device sustains on
 // the instruction mix of one 32x32 block of scores, with everything else taken away.  The
 // loops below work on registers only (operands are made up from the lane number, results are
 // reduced to one word per thread that is stored at the end), two waves per SIMD like the real
@@ -6,7 +6,7 @@
 #include <hip/hip_ext.h>
 #include <hip/hip_runtime.h>
 
-#include "../../include/fnn.h"
+#include "../../include/fnn_measure.h"
 #include "fnn_device.hpp"
 
 namespace fnn {
@@ -35,7 +35,10 @@ __device__ __forceinline__ _Float16 ceil_operand(uint32_t i) {
 // (a 32-channel block).  3: MIX 1 plus the eight 3-input maxima that fold a block into a running
 // best (the search kernel's arithmetic).  4: MIX 1 plus sixteen 3-input maxima per block, a fold
 // and a running element-wise maximum over pairs of blocks (the dense kernel's arithmetic).
-template <int MIX>
+// 5: the 32x32 block as four 16x16x32 instructions (24 channels padded to 32).
+// BF16: the same loops on the bfloat16 instructions (MIX 1, 3, 4).
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+template <int MIX, bool BF16>
 __global__ __launch_bounds__(CEIL_THREADS) __attribute__((amdgpu_waves_per_eu(2)))
 void ceiling_kernel(float* out, int trips) {
     const int lane = threadIdx.x & 63;
@@ -51,6 +54,17 @@ void ceiling_kernel(float* out, int trips) {
 #pragma unroll
         for (int r = 0; r < CEIL_R; ++r) q[r][e] = ceil_operand(2000 + (r * 64 + lane) * 8 + e);
     }
+    if constexpr (BF16) {
+        // the same bit patterns read as bfloat16 would be tiny numbers with a 7-bit significand
+        // pattern of their own; convert the values instead (bf16 keeps 8 significant bits)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            cand[e] = __builtin_bit_cast(_Float16, (__bf16)(float)cand[e]);
+            cand2[e] = __builtin_bit_cast(_Float16, (__bf16)(float)cand2[e]);
+#pragma unroll
+            for (int r = 0; r < CEIL_R; ++r) q[r][e] = __builtin_bit_cast(_Float16, (__bf16)(float)q[r][e]);
+        }
+    }
     float best[CEIL_R];
     f32x16 cmax[CEIL_R / 2];
 #pragma unroll
@@ -63,24 +77,54 @@ void ceiling_kernel(float* out, int trips) {
     // one block: the matrix instructions of MIX on operands (cand, cand2) x q
     auto block = [&](const f16x8& q_r) {
         const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-        f32x16 acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(cand, q_r, zero, 0, 0, 0);
-        if constexpr (MIX == 1 || MIX == 3 || MIX == 4) {
+        if constexpr (MIX == 5) {
+            // four 16x16 quadrants, K = 32 each; the second operand pair stands for the other
+            // 16 candidates / 16 queries of the block
+            const f32x4 z4 = {0.f, 0.f, 0.f, 0.f};
+            const f32x4 a0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(cand, q_r, z4, 0, 0, 0);
+            const f32x4 a1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(cand2, q_r, z4, 0, 0, 0);
+            const f32x4 a2 = __builtin_amdgcn_mfma_f32_16x16x32_f16(cand, cand2, z4, 0, 0, 0);
+            const f32x4 a3 = __builtin_amdgcn_mfma_f32_16x16x32_f16(cand2, cand, z4, 0, 0, 0);
+            f32x16 acc;
+#pragma unroll
+            for (int v = 0; v < 4; ++v) {
+                acc[v] = a1[v];
+                acc[4 + v] = a2[v];
+                acc[8 + v] = a3[v];
+                acc[12 + v] = a0[v];
+            }
+            return acc;
+        } else if constexpr (BF16) {
+            f32x16 acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, cand),
+                                                                 __builtin_bit_cast(bf16x8, q_r), zero, 0, 0, 0);
             const f16x4 ch = {cand2[0], cand2[1], cand2[2], cand2[3]}, qh = {q_r[4], q_r[5], q_r[6], q_r[7]};
-            acc = __builtin_amdgcn_mfma_f32_32x32x8f16(ch, qh, acc, 0, 0, 0);
-        } else if constexpr (MIX == 2) {
-            acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(cand2, q_r, acc, 0, 0, 0);
+            acc = __builtin_amdgcn_mfma_f32_32x32x8bf16_1k(__builtin_bit_cast(i16x4, ch), __builtin_bit_cast(i16x4, qh),
+                                                           acc, 0, 0, 0);
+            return acc;
+        } else {
+            f32x16 acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(cand, q_r, zero, 0, 0, 0);
+            if constexpr (MIX == 1 || MIX == 3 || MIX == 4) {
+                const f16x4 ch = {cand2[0], cand2[1], cand2[2], cand2[3]}, qh = {q_r[4], q_r[5], q_r[6], q_r[7]};
+                acc = __builtin_amdgcn_mfma_f32_32x32x8f16(ch, qh, acc, 0, 0, 0);
+            } else if constexpr (MIX == 2) {
+                acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(cand2, q_r, acc, 0, 0, 0);
+            }
+            return acc;
         }
-        return acc;
     };
 
-    if constexpr (MIX < 3) {
+    if constexpr (MIX < 3 || MIX == 5) {
         for (int trip = 0; trip < trips; ++trip) {
             // the operands are "new" every trip as far as the compiler can tell, so no product is hoisted
             asm volatile("" : "+v"(cand), "+v"(cand2));
 #pragma unroll
             for (int r = 0; r < CEIL_R; ++r) {
                 const f32x16 acc = block(q[r]);
-                best[r] = __builtin_fmaxf(best[r], acc[0]);  // one operation keeps the block alive
+                if constexpr (MIX == 5) {  // one operation per instruction keeps all four alive
+                    best[r] = ceil_max3(best[r], ceil_max3(acc[0], acc[4], acc[8]), acc[12]);
+                } else {
+                    best[r] = __builtin_fmaxf(best[r], acc[0]);  // one operation keeps the block alive
+                }
             }
         }
     } else {
@@ -118,7 +162,7 @@ void ceiling_kernel(float* out, int trips) {
     out[(size_t)blockIdx.x * CEIL_THREADS + threadIdx.x] = word;
 }
 
-template <int MIX>
+template <int MIX, bool BF16 = false>
 hipError_t run_ceiling(float* out, int grid, int trips, hipStream_t s, float* ms) {
     hipEvent_t e0, e1;
     if (hipEventCreate(&e0) != hipSuccess) return hipErrorUnknown;
@@ -126,11 +170,11 @@ hipError_t run_ceiling(float* out, int grid, int trips, hipStream_t s, float* ms
         (void)hipEventDestroy(e0);
         return hipErrorUnknown;
     }
-    hipLaunchKernelGGL(ceiling_kernel<MIX>, dim3(grid), dim3(CEIL_THREADS), 0, s, out, 16);  // warm-up
+    hipLaunchKernelGGL((ceiling_kernel<MIX, BF16>), dim3(grid), dim3(CEIL_THREADS), 0, s, out, 16);  // warm-up
     hipError_t err = hipGetLastError();
     float best = 0.f;
     for (int rep = 0; rep < 3 && err == hipSuccess; ++rep) {
-        hipExtLaunchKernelGGL(ceiling_kernel<MIX>, dim3(grid), dim3(CEIL_THREADS), 0, s, e0, e1, 0, out, trips);
+        hipExtLaunchKernelGGL((ceiling_kernel<MIX, BF16>), dim3(grid), dim3(CEIL_THREADS), 0, s, e0, e1, 0, out, trips);
         err = hipGetLastError();
         if (err == hipSuccess) err = hipEventSynchronize(e1);
         float t = 0.f;
@@ -153,7 +197,7 @@ int32_t fnn_measure_ceiling(int32_t mix, int32_t blocks_per_wave, void* scratch,
                             float* ns_per_block, void* stream) {
     using namespace fnn;
     if (!scratch || !ns_per_block) return FNN_E_NULL;
-    if (mix < 0 || mix > 4 || blocks_per_wave < CEIL_R || blocks_per_wave > (1 << 24)) return FNN_E_RANGE;
+    if (mix < 0 || mix > 8 || blocks_per_wave < CEIL_R || blocks_per_wave > (1 << 24)) return FNN_E_RANGE;
     int dev = 0;
     hipDeviceProp_t prop;
     if (hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess) return FNN_E_HIP;
@@ -169,7 +213,11 @@ int32_t fnn_measure_ceiling(int32_t mix, int32_t blocks_per_wave, void* scratch,
         case 1: err = run_ceiling<1>(out, grid, trips, s, &ms); break;
         case 2: err = run_ceiling<2>(out, grid, trips, s, &ms); break;
         case 3: err = run_ceiling<3>(out, grid, trips, s, &ms); break;
-        default: err = run_ceiling<4>(out, grid, trips, s, &ms); break;
+        case 4: err = run_ceiling<4>(out, grid, trips, s, &ms); break;
+        case 5: err = run_ceiling<5>(out, grid, trips, s, &ms); break;
+        case 6: err = run_ceiling<1, true>(out, grid, trips, s, &ms); break;
+        case 7: err = run_ceiling<3, true>(out, grid, trips, s, &ms); break;
+        default: err = run_ceiling<4, true>(out, grid, trips, s, &ms); break;
     }
     if (err != hipSuccess) return FNN_E_HIP;
     // a SIMD works on two waves' blocks at once

@@ -1,4 +1,4 @@
-// All-pairs mutual nearest neighbours (paper section 3.2, "Problem Context"): every score
+// All-pairs mutual nearest neighbours (paper section 3.2.5, "Problem Context"): every score
 // S[i][j] = <D1[i], D2[j]> is formed exactly once on the matrix cores and folded, while it
 // is still in a register, into BOTH running maxima -- the best candidate j of query i and
 // the best query i of candidate j -- so the quadratic score matrix never exists in memory.

@@ -4,11 +4,38 @@
 #include <stddef.h>
 #include <stdint.h>
 
+#include <mutex>
+
 #include "../../include/fnn.h"
 
 namespace fnn {
 
 typedef unsigned long long u64;
+
+// A launch shape that depends on the device (how many workgroups of a kernel it holds, how much
+// LDS it grants): computed once per device by the first call made with that device current, under
+// a lock, so that host threads and devices may make their first calls concurrently.
+struct DeviceCache {
+    static constexpr int MAX_DEVICES = 64;
+    std::mutex mu;
+    bool filled[MAX_DEVICES] = {};
+    long long value[MAX_DEVICES] = {};
+    // compute(device) returns the value, negative = failed (reported, not cached)
+    template <typename F>
+    long long get(F&& compute) {
+        int dev = 0;
+        if (hipGetDevice(&dev) != hipSuccess) return -1;
+        if (dev < 0 || dev >= MAX_DEVICES) return compute(dev);
+        std::lock_guard<std::mutex> lock(mu);
+        if (!filled[dev]) {
+            const long long v = compute(dev);
+            if (v < 0) return v;
+            value[dev] = v;
+            filled[dev] = true;
+        }
+        return value[dev];
+    }
+};
 
 // Padded channel count of a prepared map: 16-bit formats use one K=16 matrix instruction,
 // a K=16 and a K=8 one (24 channels, no padding for the paper's d = 24) or two K=16 ones;

@@ -1,7 +1,7 @@
 // The step after the matching path: the match set M, which the search kernels hold as flat
 // pixel ids, written the way the problem statement writes a correspondence (section 3.1,
 // "Problem Statement"): i = (w_i, h_i), j = (w_j, h_j), with an optional filter on the
-// confidence maps that the regression heads emit next to the pointmaps (section 3.1.3).
+// confidence maps that the regression heads emit next to the pointmaps (section 3.2.3).
 #include "fnn_device.hpp"
 #include "fnn_kernels.hpp"
 #include "trace.hpp"
@@ -9,6 +9,15 @@
 namespace fnn {
 
 constexpr int PIXEL_THREADS = 1024;
+
+// conf >= threshold as an ordered comparison that does not rely on how the compiler treats
+// NaN (the library is built with the assumption that scores are finite): a NaN on either side
+// is recognised from its bits and fails the test.
+__device__ __forceinline__ bool confident(float conf, float threshold) {
+    const uint32_t cb = __float_as_uint(conf) & 0x7FFFFFFFu, tb = __float_as_uint(threshold) & 0x7FFFFFFFu;
+    if (cb > 0x7F800000u || tb > 0x7F800000u) return false;
+    return conf >= threshold;
+}
 
 // One workgroup per image pair walks the pair list in chunks of 1024; a prefix sum over the
 // "kept" flags gives every surviving match its slot, so the output keeps the input order.
@@ -30,8 +39,8 @@ __global__ __launch_bounds__(PIXEL_THREADS) void pairs_to_pixels_kernel(PixelArg
             i = pairs[2 * p];
             j = pairs[2 * p + 1];
             keep = i >= 0 && i < a.n && j >= 0 && j < a.m;
-            if (keep && c1) keep = c1[i] >= a.min_conf1;  // a NaN confidence drops the match
-            if (keep && c2) keep = c2[j] >= a.min_conf2;
+            if (keep && c1) keep = confident(c1[i], a.min_conf1);  // a NaN confidence drops the match
+            if (keep && c2) keep = confident(c2[j], a.min_conf2);
         }
         int total;
         const int before = block_scan_flag(keep, wave_sums, total);

@@ -1,4 +1,4 @@
-// Bookkeeping of the FastNN iteration (paper section 3.2, "FastNN Algorithm", steps 1-4):
+// Bookkeeping of the FastNN iteration (paper section 3.2.5, "FastNN Algorithm", steps 1-4):
 // the reciprocity test U^{t+1} == U^t, the removal of converged seeds by a prefix-sum
 // compaction of the ones still moving, and the final reduction of the matches to a sorted
 // set (a distribution sort over the pixel range).  Everything lives on the device: the host enqueues a fixed sequence of kernels and
@@ -197,22 +197,20 @@ hipError_t launch_recip_step(const RecipState& st, int which, int32_t n_seeds, i
 // the default): what the device grants one workgroup, less the kernel's static LDS and some
 // slack, raised once through the kernel's attribute.
 static size_t dedup_large_lds_limit() {
-    static long long limit = -1;
-    if (limit < 0) {
-        int dev = 0, per_block = 0;
-        limit = 0;
-        if (hipGetDevice(&dev) == hipSuccess &&
-            hipDeviceGetAttribute(&per_block, hipDeviceAttributeMaxSharedMemoryPerBlock, dev) == hipSuccess &&
-            per_block > 64 * 1024) {
-            const int grant = per_block - 1024;
-            if (hipFuncSetAttribute(reinterpret_cast<const void*>(recip_dedup_kernel<true, uint16_t>),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, grant) == hipSuccess)
-                limit = grant;
-            else
-                (void)hipGetLastError();  // not granted: the workspace variant serves these sizes
-        }
-    }
-    return (size_t)limit;
+    static DeviceCache limit;
+    const long long granted = limit.get([](int dev) -> long long {
+        int per_block = 0;
+        if (hipDeviceGetAttribute(&per_block, hipDeviceAttributeMaxSharedMemoryPerBlock, dev) != hipSuccess ||
+            per_block <= 64 * 1024)
+            return 0;
+        const int grant = per_block - 1024;
+        if (hipFuncSetAttribute(reinterpret_cast<const void*>(recip_dedup_kernel<true, uint16_t>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, grant) == hipSuccess)
+            return grant;
+        (void)hipGetLastError();  // not granted: the workspace variant serves these sizes
+        return 0;
+    });
+    return granted > 0 ? (size_t)granted : 0;
 }
 
 hipError_t launch_recip_dedup(const RecipState& st, int32_t n_seeds, int batch,

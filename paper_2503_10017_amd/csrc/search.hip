@@ -55,17 +55,124 @@ __device__ __forceinline__ int64_t query_row(const SearchArgs& a, int64_t qbase,
     return min(max(row, (int64_t)0), (int64_t)a.src_rows - 1);  // never read outside the map
 }
 
-// Pass 1: per query the best score and the 32-candidate TILE that holds it.  A lane only
-// keeps a running maximum (3-input max) and, once per tile, notes the tile when the
-// maximum rose -- strictly, so the lowest tile wins among equal scores.  The key written
-// here carries the tile number in its index field; pass 2 turns it into the candidate index.
-// (waves_per_eu >= 2 caps the kernel at 256 registers, which lets the matrix instructions
-// write their results straight into ordinary vector registers.)
+// One unit of pass 1: the query blocks of slots [slot0, slot0 + 32*R*G) against the candidate
+// tiles [t0, t1).  Per query the best score and the 32-candidate TILE that holds it: a lane only
+// keeps a running maximum (3-input max) and, once per tile, notes the tile when the maximum
+// rose -- strictly, so the lowest tile wins among equal scores.  The key carries the tile
+// number in its index field; pass 2 turns it into the candidate index.  With `combine` the
+// keys go to the workgroup's table in LDS (slot0 is 0 then), else to the global table.
+// P candidate tiles are always in flight towards the registers; a slot is refilled as soon
+// as its tile has been handed to the matrix cores.  EXACT: loads past the end of the chunk are
+// skipped (for chunks that may be shorter than the ring); otherwise they re-read the chunk's
+// last tile, which keeps the loop free of branches around the loads.
+template <int CT, int DP, int R, int P, int G, bool EXACT>
+__device__ __forceinline__ void search_unit(const SearchArgs& a, const char* src, const char* tgt, int64_t qbase,
+                                            int n_act, int slot0, int t0, int t1, bool combine, u64* wg_keys, int c, int h) {
+    using O = Ops<CT, DP>;
+    using Frag = typename O::Frag;
+    const float ninf = -__builtin_inff();
+    // The first P loads are issued before the (dependent) query fetch so that both latencies
+    // overlap.
+    Frag ring[P];
+#pragma unroll
+    for (int p = 0; p < P; ++p) {
+        if (!EXACT) ring[p] = O::load_tile(tgt + (int64_t)min(t0 + p, t1 - 1) * (32 * O::ROW_BYTES), c, h);
+        else if (p == 0 || t0 + p < t1)  // uniform; a slot past the end is never used
+            ring[p] = O::load_tile(tgt + (int64_t)(t0 + p) * (32 * O::ROW_BYTES), c, h);
+    }
+
+    // blocks past the live queries of the last row group are computed on row 0 and dropped;
+    // a whole group of R blocks past them is skipped
+    Frag q[G][R];
+    float best[G][R];
+    int best_tile[G][R];
+    bool live[G];
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+        live[g] = slot0 + g * 32 * R < n_act;  // uniform
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            const int slot = slot0 + (g * R + r) * 32 + c;
+            const int64_t row = slot < n_act ? query_row(a, qbase, slot) : 0;
+            q[g][r] = O::load(src + row * O::ROW_BYTES, h);
+            best[g][r] = ninf;
+            best_tile[g][r] = 0x7FFFFFFF;
+        }
+    }
+
+    for (int tb = t0; tb < t1; tb += P) {
+#pragma unroll
+        for (int p = 0; p < P; ++p) {
+            const int t = tb + p;
+            if (t < t1) {  // uniform
+                const Frag cur = ring[p];
+                if (!EXACT) ring[p] = O::load_tile(tgt + (int64_t)min(t + P, t1 - 1) * (32 * O::ROW_BYTES), c, h);
+                else if (t + P < t1) ring[p] = O::load_tile(tgt + (int64_t)(t + P) * (32 * O::ROW_BYTES), c, h);
+#pragma unroll
+                for (int g = 0; g < G; ++g) {
+                    if (live[g]) {
+                        f32x16 acc[R];
+#pragma unroll
+                        for (int r = 0; r < R; ++r) acc[r] = O::mma(cur, q[g][r]);
+                        if (t * 32 + 32 > a.m) {  // only the last tile of the map can be partial
+                            // candidate t*32 + tile_row(v, h) lies past the map; tested against one
+                            // lane-dependent bound so that no per-register constants stay resident
+                            const int bound = a.m - t * 32 - 4 * h;
+#pragma unroll
+                            for (int r = 0; r < R; ++r)
+#pragma unroll
+                                for (int v = 0; v < 16; ++v)
+                                    if (tile_row(v, 0) >= bound) acc[r][v] = ninf;
+                        }
+#pragma unroll
+                        for (int r = 0; r < R; ++r) {
+                            const float top = fold16(best[g][r], acc[r]);
+                            if (top > best[g][r]) best_tile[g][r] = t;
+                            best[g][r] = top;
+                        }
+                    }
+                }
+            }
+        }
+    }
+
+#pragma unroll
+    for (int g = 0; g < G; ++g)
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            const float ob = __shfl_xor(best[g][r], 32);
+            const int ot = __shfl_xor(best_tile[g][r], 32);
+            if (ob > best[g][r] || (ob == best[g][r] && ot < best_tile[g][r])) {
+                best[g][r] = ob;
+                best_tile[g][r] = ot;
+            }
+            const int slot = slot0 + (g * R + r) * 32 + c;
+            if (h == 0 && slot < n_act) {
+                const u64 key = pack_key(best[g][r], best_tile[g][r]);
+                if (combine) atomicMax(&wg_keys[slot], key);
+                else atomicMax(&a.out_keys[qbase + slot], key);
+            }
+        }
+}
+
+// Candidate tiles a wave keeps in flight when a pair has at most 32*R live queries (NB = blocks
+// that hold one).  Such a search is bound by streaming the candidate map, not by arithmetic,
+// and what limits a stream is the number of bytes on their way: the registers that the resident
+// query blocks of the wide variants would occupy hold a longer ring instead.  Rows wider than
+// 96 bytes keep the ordinary ring (their fragments leave no room).
+template <int CT, int DP, int NB>
+constexpr int stream_ring() {
+    constexpr int frag_regs = Ops<CT, DP>::ROW_BYTES / 8;
+    constexpr int fit = (NB <= 2 ? 96 : 72) / frag_regs;
+    constexpr int base = Ops<CT, DP>::ROW_BYTES > 128 ? 2 : SEARCH_P;
+    return frag_regs > 12 ? base : (fit > 16 ? 16 : (fit < base ? base : fit));
+}
+
+// Pass 1 kernel.  (waves_per_eu >= 2 caps the kernel at 256 registers, which lets the matrix
+// instructions write their results straight into ordinary vector registers.)
 template <int CT, int DP, int R, int P, int G>
 __global__ __launch_bounds__(SEARCH_WAVES * 64) __attribute__((amdgpu_waves_per_eu(2)))
 void search_kernel(SearchArgs a) {
-    using O = Ops<CT, DP>;
-    using Frag = typename O::Frag;
     const int lane = threadIdx.x & 63, c = lane & 31, h = lane >> 5;
     // Workgroups are dealt to the 8 XCDs round-robin by their linear id, and each XCD has
     // its own L2.  Renumber them so that every XCD owns one contiguous run of (pair, unit)
@@ -90,7 +197,6 @@ void search_kernel(SearchArgs a) {
     const char* src = a.src + (int64_t)b * a.src_bstride;
     const char* tgt = a.tgt + (int64_t)b * a.tgt_bstride;
     const int64_t qbase = (int64_t)b * a.nq;
-    const float ninf = -__builtin_inff();
 
     // With a single row group every unit of this pair serves the same queries, so the waves of
     // a workgroup first merge their results in LDS and the workgroup sends one atomic per query
@@ -109,85 +215,20 @@ void search_kernel(SearchArgs a) {
         const int chunk = (int)(unit / row_groups);
         const int rg = (int)(unit % row_groups);
         const int slot0 = rg * 32 * R * G;
-
         const int t0 = chunk * tiles_per_chunk;
         const int t1 = min(t0 + tiles_per_chunk, a.m_tiles);
-        // P candidate tiles are always in flight towards the registers; a slot is refilled
-        // as soon as its tile has been handed to the matrix cores.  The first P loads are
-        // issued before the (dependent) query fetch so that both latencies overlap.
-        Frag ring[P];
-#pragma unroll
-        for (int p = 0; p < P; ++p)
-            ring[p] = O::load_tile(tgt + (int64_t)min(t0 + p, t1 - 1) * (32 * O::ROW_BYTES), c, h);
-
-        // blocks past the live queries of the last row group are computed on row 0 and dropped;
-        // a whole group of R blocks past them is skipped
-        Frag q[G][R];
-        float best[G][R];
-        int best_tile[G][R];
-        bool live[G];
-#pragma unroll
-        for (int g = 0; g < G; ++g) {
-            live[g] = slot0 + g * 32 * R < n_act;  // uniform
-#pragma unroll
-            for (int r = 0; r < R; ++r) {
-                const int slot = slot0 + (g * R + r) * 32 + c;
-                const int64_t row = slot < n_act ? query_row(a, qbase, slot) : 0;
-                q[g][r] = O::load(src + row * O::ROW_BYTES, h);
-                best[g][r] = ninf;
-                best_tile[g][r] = 0x7FFFFFFF;
-            }
+        if (n_act <= 32 * R) {
+            // few live queries (one row group, so combine is set): only the blocks that hold a
+            // live query are multiplied, and the ring is as long as the registers allow
+            if (n_act <= 32)
+                search_unit<CT, DP, 1, stream_ring<CT, DP, 1>(), 1, true>(a, src, tgt, qbase, n_act, 0, t0, t1, true, wg_keys, c, h);
+            else if (n_act <= 64)
+                search_unit<CT, DP, 2, stream_ring<CT, DP, 2>(), 1, true>(a, src, tgt, qbase, n_act, 0, t0, t1, true, wg_keys, c, h);
+            else
+                search_unit<CT, DP, R, stream_ring<CT, DP, R>(), 1, true>(a, src, tgt, qbase, n_act, 0, t0, t1, true, wg_keys, c, h);
+        } else {
+            search_unit<CT, DP, R, P, G, false>(a, src, tgt, qbase, n_act, slot0, t0, t1, combine, wg_keys, c, h);
         }
-
-        for (int tb = t0; tb < t1; tb += P) {
-#pragma unroll
-            for (int p = 0; p < P; ++p) {
-                const int t = tb + p;
-                if (t < t1) {  // uniform
-                    const Frag cur = ring[p];
-                    ring[p] = O::load_tile(tgt + (int64_t)min(t + P, t1 - 1) * (32 * O::ROW_BYTES), c, h);
-#pragma unroll
-                    for (int g = 0; g < G; ++g) {
-                        if (live[g]) {
-                            f32x16 acc[R];
-#pragma unroll
-                            for (int r = 0; r < R; ++r) acc[r] = O::mma(cur, q[g][r]);
-                            if (t * 32 + 32 > a.m) {  // only the last tile of the map can be partial
-#pragma unroll
-                                for (int r = 0; r < R; ++r)
-#pragma unroll
-                                    for (int v = 0; v < 16; ++v)
-                                        if (t * 32 + tile_row(v, h) >= a.m) acc[r][v] = ninf;
-                            }
-#pragma unroll
-                            for (int r = 0; r < R; ++r) {
-                                const float top = fold16(best[g][r], acc[r]);
-                                if (top > best[g][r]) best_tile[g][r] = t;
-                                best[g][r] = top;
-                            }
-                        }
-                    }
-                }
-            }
-        }
-
-#pragma unroll
-        for (int g = 0; g < G; ++g)
-#pragma unroll
-            for (int r = 0; r < R; ++r) {
-                const float ob = __shfl_xor(best[g][r], 32);
-                const int ot = __shfl_xor(best_tile[g][r], 32);
-                if (ob > best[g][r] || (ob == best[g][r] && ot < best_tile[g][r])) {
-                    best[g][r] = ob;
-                    best_tile[g][r] = ot;
-                }
-                const int slot = slot0 + (g * R + r) * 32 + c;
-                if (h == 0 && slot < n_act) {
-                    const u64 key = pack_key(best[g][r], best_tile[g][r]);
-                    if (combine) atomicMax(&wg_keys[slot], key);  // slot0 == 0 here: slot < 32 * R * G
-                    else atomicMax(&a.out_keys[qbase + slot], key);
-                }
-            }
     }
     if (combine) {
         __syncthreads();
@@ -269,18 +310,19 @@ constexpr int search_g_limit() {
 }
 template <int CT, int DP>
 static int search_wgs_per_pair(int batch) {
-    static int resident_wgs = 0;
-    if (resident_wgs == 0) {
-        int per_cu = 0, dev = 0;
+    static DeviceCache resident_wgs;  // workgroups of the widest variant the current device holds at once
+    const long long resident = resident_wgs.get([](int dev) -> long long {
+        int per_cu = 0;
         hipDeviceProp_t prop;
         if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu,
                                                          search_kernel<CT, DP, SEARCH_R, search_ring<CT, DP>(), search_g_limit<CT, DP>()>,
                                                          SEARCH_WAVES * 64, 0) != hipSuccess ||
-            hipGetDevice(&dev) != hipSuccess || hipGetDeviceProperties(&prop, dev) != hipSuccess)
-            return 0;
-        resident_wgs = (per_cu > 0 ? per_cu : 1) * prop.multiProcessorCount;
-    }
-    int wgs = resident_wgs / batch;
+            hipGetDeviceProperties(&prop, dev) != hipSuccess)
+            return -1;
+        return (long long)(per_cu > 0 ? per_cu : 1) * prop.multiProcessorCount;
+    });
+    if (resident <= 0) return 0;
+    int wgs = (int)resident / batch;
     if (wgs >= 8) wgs &= ~7;  // a multiple of 8 per pair keeps the XCD renumbering a bijection
     return wgs < 1 ? 1 : wgs;
 }
@@ -302,7 +344,7 @@ static hipError_t launch_search_g(const SearchArgs& a, int batch, hipStream_t s)
                               ((a.m_tiles + SEARCH_MIN_TILES - 1) / SEARCH_MIN_TILES);
     const int64_t need = (max_units + SEARCH_WAVES - 1) / SEARCH_WAVES;
     if (need < wgs) wgs = (int)(need > 0 ? need : 1);
-    return launch(TK_SEARCH, search_kernel<CT, DP, SEARCH_R, search_ring<CT, DP>(), G>, dim3(wgs, batch), dim3(SEARCH_WAVES * 64), 0, s, a);
+    return launch_detail(TK_SEARCH, G, search_kernel<CT, DP, SEARCH_R, search_ring<CT, DP>(), G>, dim3(wgs, batch), dim3(SEARCH_WAVES * 64), 0, s, a);
 }
 
 template <int CT, int DP>

@@ -1,9 +1,9 @@
-// Measurement aid behind fnn_trace_begin / fnn_trace_end (see include/fnn.h).
+// Measurement aid behind fnn_trace_begin / fnn_trace_end (see include/fnn_measure.h).
 #include "trace.hpp"
 
 #include <vector>
 
-#include "../../include/fnn.h"
+#include "../../include/fnn_measure.h"
 
 namespace fnn {
 
@@ -12,16 +12,17 @@ struct TraceState {
     bool open = false;
     int used = 0;
     std::vector<hipEvent_t> start, stop;
-    std::vector<int> kind;
+    std::vector<int> kind, detail;
 };
 TraceState g_trace;
 }  // namespace
 
-bool trace_next(int kind, hipEvent_t* start, hipEvent_t* stop) {
+bool trace_next(int kind, int detail, hipEvent_t* start, hipEvent_t* stop) {
     if (!g_trace.open || g_trace.used >= (int)g_trace.start.size()) return false;
     *start = g_trace.start[g_trace.used];
     *stop = g_trace.stop[g_trace.used];
     g_trace.kind[g_trace.used] = kind;
+    g_trace.detail[g_trace.used] = detail;
     ++g_trace.used;
     return true;
 }
@@ -32,6 +33,7 @@ static void trace_release() {
     g_trace.start.clear();
     g_trace.stop.clear();
     g_trace.kind.clear();
+    g_trace.detail.clear();
     g_trace.used = 0;
     g_trace.open = false;
 }
@@ -49,6 +51,7 @@ int32_t fnn_trace_begin(int32_t max_kernels) {
     g_trace.start.resize(max_kernels);
     g_trace.stop.resize(max_kernels);
     g_trace.kind.assign(max_kernels, -1);
+    g_trace.detail.assign(max_kernels, 0);
     for (int i = 0; i < max_kernels; ++i) {
         if (hipEventCreate(&g_trace.start[i]) != hipSuccess || hipEventCreate(&g_trace.stop[i]) != hipSuccess) {
             g_trace.start.resize(i);
@@ -61,7 +64,7 @@ int32_t fnn_trace_begin(int32_t max_kernels) {
     return FNN_OK;
 }
 
-int32_t fnn_trace_end(int32_t capacity, int32_t* kinds, float* milliseconds, int32_t* n_recorded) {
+int32_t fnn_trace_end(int32_t capacity, int32_t* kinds, float* milliseconds, int32_t* details, int32_t* n_recorded) {
     if (!n_recorded || (capacity > 0 && (!kinds || !milliseconds))) return FNN_E_NULL;
     int32_t status = FNN_OK;
     const int n = g_trace.used;
@@ -72,6 +75,7 @@ int32_t fnn_trace_end(int32_t capacity, int32_t* kinds, float* milliseconds, int
             hipEventElapsedTime(&ms, g_trace.start[i], g_trace.stop[i]) != hipSuccess)
             status = FNN_E_HIP;
         kinds[i] = g_trace.kind[i];
+        if (details) details[i] = g_trace.detail[i];
         milliseconds[i] = ms;
     }
     trace_release();

@@ -25,17 +25,23 @@ enum TraceKind : int {
 };
 
 // Returns false when no trace is open or it is full; otherwise hands out the next event pair.
-bool trace_next(int kind, hipEvent_t* start, hipEvent_t* stop);
+// `detail` is a number the launcher wants reported with the kernel (the launch shape it chose).
+bool trace_next(int kind, int detail, hipEvent_t* start, hipEvent_t* stop);
 
 template <typename Kernel, typename... Args>
-inline hipError_t launch(int kind, Kernel kernel, dim3 grid, dim3 block, size_t lds_bytes, hipStream_t s, Args... args) {
+inline hipError_t launch_detail(int kind, int detail, Kernel kernel, dim3 grid, dim3 block, size_t lds_bytes,
+                                hipStream_t s, Args... args) {
     hipEvent_t e0, e1;
-    if (trace_next(kind, &e0, &e1)) {
+    if (trace_next(kind, detail, &e0, &e1)) {
         hipExtLaunchKernelGGL(kernel, grid, block, lds_bytes, s, e0, e1, 0, args...);
     } else {
         hipLaunchKernelGGL(kernel, grid, block, lds_bytes, s, args...);
     }
     return hipGetLastError();
+}
+template <typename Kernel, typename... Args>
+inline hipError_t launch(int kind, Kernel kernel, dim3 grid, dim3 block, size_t lds_bytes, hipStream_t s, Args... args) {
+    return launch_detail(kind, 0, kernel, grid, block, lds_bytes, s, args...);
 }
 
 }  // namespace fnn

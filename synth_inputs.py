@@ -5,7 +5,7 @@ matching method's arithmetic, so both the CPU oracle's tests and the GPU path's
 tests may import it.  Everything is a pure function of its integer seed.
 
 The maps stand in for the per-pixel descriptor maps D1, D2 of shape H x W x d
-that the matching head produces (paper section 3.2, "Matching Head"); the paper
+that the matching head produces (paper section 3.2.4, "Matching Head"); the paper
 evaluates on public indoor/outdoor image-pair benchmarks with pretrained
 weights, neither of which is used here.
 

@@ -1,4 +1,7 @@
 """Shared pieces of the GPU parity tests (which call the HIP library through its C ABI)."""
+import hashlib
+import os
+
 import numpy as np
 import torch
 
@@ -6,6 +9,35 @@ import oracle
 import paper_2503_10017_amd as fnn
 
 DEV = torch.device("cuda:0")
+
+# Oracle results of the large configurations are kept on disk between runs, keyed by a hash of
+# the inputs (the files are written by this module from oracle/ alone and are not tracked).
+ORACLE_CACHE = os.environ.get("FNN_ORACLE_CACHE",
+                              os.path.join(os.path.dirname(os.path.abspath(__file__)), ".oracle_cache"))
+
+
+def cached_mutual_dense(a, b, tag):
+    """oracle.mutual_dense(a, b), its arrays cached on disk under a key made of the input bytes."""
+    h = hashlib.sha1()
+    h.update(tag.encode())
+    h.update(np.ascontiguousarray(a).tobytes())
+    h.update(np.ascontiguousarray(b).tobytes())
+    path = os.path.join(ORACLE_CACHE, f"mutual_dense_{tag}_{h.hexdigest()[:20]}.npz")
+    keys = ("nn12", "s12", "gap12", "nn21", "s21", "gap21", "pairs")
+    if os.path.exists(path):
+        with np.load(path) as z:
+            if all(k in z.files for k in keys):
+                return {k: z[k] for k in keys}
+    ref = oracle.mutual_dense(a, b)
+    ref = {k: ref[k] for k in keys}
+    try:
+        os.makedirs(ORACLE_CACHE, exist_ok=True)
+        tmp = path + f".tmp{os.getpid()}.npz"
+        np.savez(tmp, **ref)
+        os.replace(tmp, path)
+    except OSError:
+        pass  # a read-only tree: recompute next time
+    return ref
 
 # Index parity thresholds on Gaussian workloads: the GPU must return the oracle's index
 # wherever the oracle's top-1/top-2 gap exceeds this (16-bit compute: input rounding moves
@@ -89,13 +121,13 @@ def check_reciprocal_exact(got, b, ref):
     assert np.all(got["pairs"][b, n_pairs:] == -1)
 
 
-def check_reciprocal_pinned(got, b, ref, d1, d2, gap_thr, what=""):
+def check_reciprocal_pinned(got, b, ref, d1, d2, gap_thr, what="", min_pinned=0.9):
     """Seeds whose whole oracle walk had clear gaps must match exactly; the rest must still be
     consistent: the pair list is exactly the sorted set of the converged seeds' pairs, and
     every returned pair is mutually nearest up to the gap threshold."""
     gi, gj, gt = got["seed_i"][b], got["seed_j"][b], got["seed_iter"][b]
     pinned = ref["min_gap"] > gap_thr
-    assert pinned.mean() > 0.5, f"{what}: only {pinned.mean():.2f} of the seeds are pinned"
+    assert pinned.mean() >= min_pinned, f"{what}: only {pinned.mean():.2f} of the seeds are pinned"
     for name, g, r in (("seed_i", gi, ref["seed_i"]), ("seed_j", gj, ref["seed_j"]), ("seed_iter", gt, ref["seed_iter"])):
         bad = pinned & (g != r)
         assert not bad.any(), f"{what}: {name} differs for {bad.sum()} pinned seeds (first {np.nonzero(bad)[0][:5]})"

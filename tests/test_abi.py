@@ -22,8 +22,8 @@ def lib():
     return fnn.load_library()
 
 
-def declared_functions():
-    with open(os.path.join(ROOT, "include", "fnn.h")) as f:
+def declared_functions(header="fnn.h"):
+    with open(os.path.join(ROOT, "include", header)) as f:
         text = f.read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     return sorted(set(re.findall(r"\b(fnn_[a-z_]+)\s*\(", text)))
@@ -31,10 +31,12 @@ def declared_functions():
 
 def test_every_declared_symbol_is_exported(lib):
     names = declared_functions()
-    assert names == ["fnn_blocked_workspace_bytes", "fnn_measure_ceiling", "fnn_mutual_dense", "fnn_nearest", "fnn_nearest_blocked",
-                     "fnn_pairs_to_pixels", "fnn_reciprocal", "fnn_status_string", "fnn_trace_begin", "fnn_trace_end", "fnn_trace_kind_name",
+    assert names == ["fnn_blocked_workspace_bytes", "fnn_mutual_dense", "fnn_nearest", "fnn_nearest_blocked",
+                     "fnn_pairs_to_pixels", "fnn_reciprocal", "fnn_status_string",
                      "fnn_workspace_bytes", "fnn_workspace_bytes_opts"]
-    for name in names:
+    measure = declared_functions("fnn_measure.h")
+    assert measure == ["fnn_measure_ceiling", "fnn_trace_begin", "fnn_trace_end", "fnn_trace_kind_name"]
+    for name in names + measure:
         assert hasattr(lib, name), name
 
 

@@ -6,8 +6,8 @@ import torch
 import oracle
 import paper_2503_10017_amd as fnn
 import synth_inputs as synth
-from gpu_helpers import (GAP_F32, GAP_HALF, GAP_ROUNDED, ROUNDERS, SCORE_TOL, SCORE_TOL_ROUNDED, check_reciprocal_exact,
-                         check_reciprocal_pinned, dev, host, run_reciprocal)
+from gpu_helpers import (GAP_F32, GAP_HALF, GAP_ROUNDED, ROUNDERS, SCORE_TOL, SCORE_TOL_ROUNDED, cached_mutual_dense,
+                         check_reciprocal_exact, check_reciprocal_pinned, dev, host, run_reciprocal)
 
 pytestmark = pytest.mark.gpu
 
@@ -33,8 +33,8 @@ def test_config2_single_pair(compute):
     seeds = synth.grid_seeds(512, 384, 8)
     got = run_reciprocal([a], [b], seeds[None], 10, compute)
     ref = oracle.reciprocal(a, b, seeds, 10)
-    pinned = check_reciprocal_pinned(got, 0, ref, a, b, GAP_F32 if compute == "f32" else GAP_HALF, f"cfg2 {compute}")
-    assert pinned.mean() > (0.99 if compute == "f32" else 0.9)
+    check_reciprocal_pinned(got, 0, ref, a, b, GAP_F32 if compute == "f32" else GAP_HALF, f"cfg2 {compute}",
+                            min_pinned=0.99 if compute == "f32" else 0.9)
     if compute == "f16":
         ra, rb = oracle.round_fp16(a), oracle.round_fp16(b)
         ref = oracle.reciprocal(ra, rb, seeds, 10)
@@ -86,6 +86,48 @@ def _check_dense_sampled(a, b, compute, n_sample, seed):
 def test_config3_dense_fp16_sampled():
     a, b = synth.config_pair(3)
     _check_dense_sampled(a, b, "f16", 4096, 3)
+
+
+@pytest.fixture(scope="module")
+def config3_gpu():
+    a, b = synth.config_pair(3)
+    out = fnn.fnn_mutual_dense(dev(a), dev(b), compute="f16")
+    torch.cuda.synchronize()
+    return a, b, {k: host(v)[0] for k, v in out.items()}
+
+
+@pytest.mark.parametrize("inputs", ["rounded", "fp32"])
+def test_config3_dense_fp16_full(config3_gpu, inputs):
+    """Every row and every column of the 196608 x 196608 problem against the oracle: on inputs rounded
+    to fp16 the way the library rounds them (only the fp32 summation order differs) and on the fp32
+    inputs themselves (the stated tolerance).  The oracle's arrays are cached on disk by input hash."""
+    a, b, got = config3_gpu
+    if inputs == "rounded":
+        xa, xb, gap, tol = oracle.round_fp16(a), oracle.round_fp16(b), GAP_ROUNDED, SCORE_TOL_ROUNDED
+    else:
+        xa, xb, gap, tol = a, b, GAP_HALF, SCORE_TOL
+    ref = cached_mutual_dense(xa, xb, "cfg3_" + inputs)
+    for side in ("12", "21"):
+        clear = ref["gap" + side] > gap
+        assert clear.mean() > (0.99 if inputs == "rounded" else 0.9), (side, clear.mean())
+        bad = clear & (got["nn" + side] != ref["nn" + side])
+        assert not bad.any(), f"{inputs} nn{side}: {bad.sum()} indices differ where the gap is clear (first {np.nonzero(bad)[0][:5]})"
+        err = np.abs(got["s" + side] - ref["s" + side])
+        assert err.max() <= tol, f"{inputs} s{side}: max score error {err.max()}"
+    # the pair list: every oracle pair whose two searches were clear is returned, and every returned
+    # pair whose two searches were clear is an oracle pair
+    n_pairs = int(got["n_pairs"])
+    gp = got["pairs"][:n_pairs]
+    clear12, clear21 = ref["gap12"] > gap, ref["gap21"] > gap
+    want = ref["pairs"][clear12[ref["pairs"][:, 0]] & clear21[ref["pairs"][:, 1]]]
+    got_keys = gp[:, 0].astype(np.int64) * b.shape[0] + gp[:, 1]
+    want_keys = want[:, 0].astype(np.int64) * b.shape[0] + want[:, 1]
+    assert np.isin(want_keys, got_keys).all()
+    sure = gp[clear12[gp[:, 0]] & clear21[gp[:, 1]]]
+    ref_keys = ref["pairs"][:, 0].astype(np.int64) * b.shape[0] + ref["pairs"][:, 1]
+    assert np.isin(sure[:, 0].astype(np.int64) * b.shape[0] + sure[:, 1], ref_keys).all()
+    if inputs == "rounded":
+        assert len(want) > 0.99 * len(ref["pairs"])
 
 
 def test_config4_batch16():

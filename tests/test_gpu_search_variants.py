@@ -1,7 +1,8 @@
 """The search launcher picks how many query blocks a wave keeps resident (1, 2 or 4 groups of four) from the
 batch size, the query count and the candidate count.  These shapes are chosen to reach each choice on an
-MI355X (64 pairs leave 32 waves per pair; a wave takes more groups only while its chunk keeps >= 256 tiles);
-whatever is chosen, the results must be bit-identical to single-pair calls (which use one group) and to the oracle.
+MI355X (64 pairs leave 32 waves per pair; a wave takes more groups only while its chunk keeps >= 128 tiles,
+and rows wider than 48 bytes stop at two groups); the launch reports its choice through the kernel trace, and
+whatever is chosen the results must be bit-identical to single-pair calls (which use one group) and to the oracle.
 """
 import numpy as np
 import pytest
@@ -14,14 +15,30 @@ from gpu_helpers import dev, exact_maps, host
 pytestmark = pytest.mark.gpu
 
 
-@pytest.mark.parametrize("nq,m,compute,l2", [
-    (128, 262144 + 17, "f16", False),     # 8192 tiles / 32 chunks = 256 per chunk: four groups
-    (512, 160000, "f16", False),          # 5000 tiles: 156 per chunk with four groups, 312 with two
-    (512, 160000, "bf16", True),          # 32-channel rows: at most two groups
-    (128, 100000, "f32", False),          # fp32 rows of 24 channels: at most two groups (195 tiles per chunk: one)
-    (512, 40000, "f16", False),           # short chunks: one group
+def traced_nearest(*args, **kw):
+    fnn.fnn_trace_begin(16)
+    try:
+        out = fnn.fnn_nearest(*args, **kw)
+        torch.cuda.synchronize()
+    finally:
+        trace = fnn.fnn_trace_end(16, details=True)
+    groups = [detail for name, _, detail in trace if name == "search_kernel"]
+    assert len(groups) == 1
+    return out, groups[0]
+
+
+@pytest.mark.parametrize("nq,m,compute,l2,want_groups", [
+    (128, 262144 + 17, "f16", False, 4),     # 8193 tiles / 32 chunks = 256 per chunk: four groups
+    (512, 160000, "f16", False, 4),          # 5000 tiles: 156 per chunk with four groups
+    (512, 100000, "f16", False, 2),          # 3125 tiles: 97 per chunk with four groups, 195 with two
+    (512, 40000, "f16", False, 1),           # 1250 tiles: short chunks, one group
+    (512, 100000, "bf16", False, 2),
+    (512, 160000, "bf16", True, 2),          # 32-channel rows: at most two groups (312 tiles per chunk)
+    (512, 40000, "bf16", True, 1),           # 32-channel rows, 78 tiles per chunk with two groups: one
+    (128, 262144 + 17, "f32", False, 2),     # fp32 rows of 24 channels: at most two groups (256 tiles per chunk)
+    (128, 100000, "f32", False, 1),          # 97 tiles per chunk: one group
 ])
-def test_every_row_group_width_gives_the_same_answers(nq, m, compute, l2):
+def test_every_row_group_width_gives_the_same_answers(nq, m, compute, l2, want_groups):
     batch, n, d = 64, 2048, 24
     _, cand = exact_maps(900 + nq, 1, m, d)
     tb = dev(cand)
@@ -29,12 +46,12 @@ def test_every_row_group_width_gives_the_same_answers(nq, m, compute, l2):
     srcs = [rng.integers(-8, 9, size=(n, d)).astype(np.float32) / 8 for _ in range(batch)]
     q = np.stack([np.sort(rng.choice(n, nq, replace=False)) for _ in range(batch)]).astype(np.int32)
     ts = [dev(x) for x in srcs]
-    gi, gs = fnn.fnn_nearest(ts, [tb] * batch, q_idx=dev(q), compute=compute, l2=l2)
-    torch.cuda.synchronize()
+    (gi, gs), groups = traced_nearest(ts, [tb] * batch, q_idx=dev(q), compute=compute, l2=l2)
+    assert groups == want_groups, f"the launcher chose {groups} row groups per wave, the shape was built for {want_groups}"
     gi, gs = host(gi), host(gs)
     for b in (0, 17, 63):                  # single-pair calls: many waves per pair, one group per wave
-        si, ss = fnn.fnn_nearest(ts[b], tb, q_idx=dev(q[b])[None], compute=compute, l2=l2)
-        torch.cuda.synchronize()
+        (si, ss), single_groups = traced_nearest(ts[b], tb, q_idx=dev(q[b])[None], compute=compute, l2=l2)
+        assert single_groups == 1
         assert np.array_equal(gi[b], host(si)[0]) and np.array_equal(gs[b], host(ss)[0])
     for b in (0, 63):
         if l2:
