@@ -78,13 +78,13 @@ void ceiling_kernel(float* out, int trips) {
     auto block = [&](const f16x8& q_r) {
         const f32x16 zero = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
         if constexpr (MIX == 5) {
-            // four 16x16 quadrants, K = 32 each; the second operand pair stands for the other
-            // 16 candidates / 16 queries of the block
+            // four 16x16 quadrants, K = 32 each; every one takes this block's query operand (in
+            // either role) so that none can be shared between blocks or hoisted out of the loop
             const f32x4 z4 = {0.f, 0.f, 0.f, 0.f};
             const f32x4 a0 = __builtin_amdgcn_mfma_f32_16x16x32_f16(cand, q_r, z4, 0, 0, 0);
             const f32x4 a1 = __builtin_amdgcn_mfma_f32_16x16x32_f16(cand2, q_r, z4, 0, 0, 0);
-            const f32x4 a2 = __builtin_amdgcn_mfma_f32_16x16x32_f16(cand, cand2, z4, 0, 0, 0);
-            const f32x4 a3 = __builtin_amdgcn_mfma_f32_16x16x32_f16(cand2, cand, z4, 0, 0, 0);
+            const f32x4 a2 = __builtin_amdgcn_mfma_f32_16x16x32_f16(q_r, cand, z4, 0, 0, 0);
+            const f32x4 a3 = __builtin_amdgcn_mfma_f32_16x16x32_f16(q_r, cand2, z4, 0, 0, 0);
             f32x16 acc;
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
