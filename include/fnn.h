@@ -197,6 +197,29 @@ int32_t fnn_reciprocal(int32_t batch, const fnn_map* d1, const fnn_map* d2,
                        void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * fnn_reciprocal for callers that cannot allocate device memory or hand over a workspace --
+ * code running under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.
+ * Same arguments, outputs and results as fnn_reciprocal, but the workspace is an array of
+ * FNN_STATIC_SCRATCH_BYTES that the library itself holds on every device it is loaded on (a
+ * device-side global, resident until the process ends).  The call allocates nothing: no
+ * hipMalloc / hipFree and no allocating library routine; the first call on a device looks up
+ * the array's address on that device (make that call outside graph capture, like the first
+ * call of any entry point).
+ * Limit: a call that needs more workspace than FNN_STATIC_SCRATCH_BYTES -- fnn_reciprocal's share
+ * of fnn_workspace_bytes_opts(): the two prepared maps plus about 40 bytes per seed and a byte
+ * per pixel -- is rejected with FNN_E_WORKSPACE before anything is enqueued (48 MiB: one
+ * 512x384 pair with d = 24 in any compute format, or two such pairs in a 16-bit format, fit).
+ * All calls on one device share that device's array, which keeps the previous call's contents
+ * (the call clears what must start at zero itself): calls that overlap on one device -- on
+ * different streams or from different host threads -- race; order them on one stream.
+ */
+#define FNN_STATIC_SCRATCH_BYTES ((size_t)48 << 20)
+int32_t fnn_reciprocal_static(int32_t batch, const fnn_map* d1, const fnn_map* d2,
+                              const int32_t* seeds, int64_t n_seeds, const fnn_opts* opts,
+                              int32_t* seed_i, int32_t* seed_j, int32_t* seed_iter,
+                              int32_t* pairs, int32_t* n_pairs, void* stream);
+
+/*
  * All-pairs mutual nearest neighbours (section 3.2.5, "Problem Context").  With
  * S[i][j] = score(d1[i], d2[j]):
  *   nn12[b][i] = lowest j maximising S[i][j],  s12 = that score      (int32/float [batch][n])

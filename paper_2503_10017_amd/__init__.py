@@ -15,6 +15,7 @@ from .binding import (  # noqa: F401
     fnn_nearest_blocked,
     fnn_pairs_to_pixels,
     fnn_reciprocal,
+    fnn_reciprocal_static,
     fnn_status_string,
     fnn_trace_begin,
     fnn_trace_end,

@@ -61,6 +61,8 @@ def load_library():
     lib.fnn_nearest.argtypes = [i32, vp, vp, i64, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.fnn_reciprocal.restype = i32
     lib.fnn_reciprocal.argtypes = [i32, vp, vp, vp, i64, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.fnn_reciprocal_static.restype = i32
+    lib.fnn_reciprocal_static.argtypes = [i32, vp, vp, vp, i64, vp, vp, vp, vp, vp, vp, vp]
     lib.fnn_mutual_dense.restype = i32
     lib.fnn_mutual_dense.argtypes = [i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.fnn_blocked_workspace_bytes.restype = sz
@@ -222,6 +224,27 @@ def fnn_reciprocal(d1: MapsLike, d2: MapsLike, seeds: torch.Tensor, max_iter: in
                             _ptr(workspace), workspace.numel(), _stream_ptr(stream, device))
     if st != 0:
         raise FnnError(st, "fnn_reciprocal")
+    return out
+
+
+FNN_STATIC_SCRATCH_BYTES = 48 << 20
+
+
+def fnn_reciprocal_static(d1: MapsLike, d2: MapsLike, seeds: torch.Tensor, out: dict, max_iter: int = 10, compute="f16",
+                          normalize: bool = False, l2: bool = False, split: bool = False, stream=None):
+    """fnn_reciprocal on the library's own scratch array: no workspace, and this wrapper allocates
+    nothing either -- ``out`` (the dict of tensors fnn_reciprocal returns) must be passed in."""
+    lib = load_library()
+    v1, v2 = _as_pairs(d1), _as_pairs(d2)
+    batch = len(v1)
+    o = _opts(compute, max_iter, normalize, l2=l2, split=split)
+    a1, a2 = _map_array(v1), _map_array(v2)
+    st = lib.fnn_reciprocal_static(batch, ctypes.cast(a1, ctypes.c_void_p), ctypes.cast(a2, ctypes.c_void_p),
+                                   _ptr(seeds), seeds.shape[-1], ctypes.byref(o),
+                                   _ptr(out["seed_i"]), _ptr(out["seed_j"]), _ptr(out["seed_iter"]),
+                                   _ptr(out["pairs"]), _ptr(out["n_pairs"]), _stream_ptr(stream, v1[0].device))
+    if st != 0:
+        raise FnnError(st, "fnn_reciprocal_static")
     return out
 
 

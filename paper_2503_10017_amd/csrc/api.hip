@@ -1,5 +1,6 @@
 // C entry points of libfnn (see include/fnn.h): argument checks, workspace carving and the
 // fixed kernel sequences.  Nothing here synchronises with the device or allocates memory.
+#include <hip/hip_runtime.h>
 #include <string.h>
 
 #include "dense_perm.hpp"
@@ -237,6 +238,34 @@ hipError_t prep_both(int32_t batch, const fnn_map* a, const fnn_map* b, const Ma
 
 }  // namespace
 
+// ---- scratch of fnn_reciprocal_static ----------------------------------------------------------
+// One array per device (every device that loads the library holds its own copy at its own
+// address, for the life of the process).  In host code the array's name is only a handle: the
+// memory is reached through the address that hipGetSymbolAddress returns for the current device,
+// looked up once per device and kept.
+static __device__ __align__(256) unsigned char scratch[FNN_STATIC_SCRATCH_BYTES];
+
+static struct StaticScratch {
+    std::mutex mu;
+    void* ptr[DeviceCache::MAX_DEVICES] = {};
+} g_static_scratch;
+
+// Address of the current device's scratch array, or NULL (a HIP call failed).  Allocates nothing.
+static void* static_scratch_for_current_device() {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= DeviceCache::MAX_DEVICES) return nullptr;
+    std::lock_guard<std::mutex> lock(g_static_scratch.mu);
+    if (!g_static_scratch.ptr[dev]) {
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) {
+            (void)hipGetLastError();
+            return nullptr;
+        }
+        g_static_scratch.ptr[dev] = p;
+    }
+    return g_static_scratch.ptr[dev];
+}
+
 #pragma GCC visibility push(default)
 extern "C" {
 
@@ -400,9 +429,11 @@ int32_t fnn_nearest_blocked(const fnn_map* src, const int32_t* q_idx, int64_t nq
     return FNN_OK;
 }
 
-int32_t fnn_reciprocal(int32_t batch, const fnn_map* d1, const fnn_map* d2, const int32_t* seeds, int64_t n_seeds,
-                       const fnn_opts* opts, int32_t* seed_i, int32_t* seed_j, int32_t* seed_iter, int32_t* pairs,
-                       int32_t* n_pairs, void* workspace, size_t workspace_bytes, void* stream) {
+// The FastNN iteration.  use_static: the workspace is the library's own scratch array of the
+// current device (looked up only after every argument check has passed).
+static int32_t reciprocal_impl(int32_t batch, const fnn_map* d1, const fnn_map* d2, const int32_t* seeds, int64_t n_seeds,
+                               const fnn_opts* opts, int32_t* seed_i, int32_t* seed_j, int32_t* seed_iter, int32_t* pairs,
+                               int32_t* n_pairs, void* workspace, size_t workspace_bytes, bool use_static, void* stream) {
     if (batch < 1 || batch > FNN_MAX_BATCH) return FNN_E_SHAPE;
     int32_t st = check_maps(batch, d1);
     if (st != FNN_OK) return st;
@@ -420,6 +451,14 @@ int32_t fnn_reciprocal(int32_t batch, const fnn_map* d1, const fnn_map* d2, cons
     if (!n_pairs) return FNN_E_NULL;
     if (n_seeds > 0 && (!seeds || !seed_i || !seed_j || !seed_iter || !pairs)) return FNN_E_NULL;
 
+    if (use_static) {
+        Carver need{nullptr, 0};
+        carve_recip(need, batch, n, m, de, n_seeds, opts->compute);
+        if (need.used > FNN_STATIC_SCRATCH_BYTES) return FNN_E_WORKSPACE;  // before the device is touched
+        workspace = static_scratch_for_current_device();
+        if (!workspace) return FNN_E_HIP;
+        workspace_bytes = FNN_STATIC_SCRATCH_BYTES;
+    }
     Carver cv{(char*)workspace, 0};
     RecipLayout L = carve_recip(cv, batch, n, m, de, n_seeds, opts->compute);
     st = check_workspace(workspace, workspace_bytes, cv.used);
@@ -499,6 +538,20 @@ int32_t fnn_reciprocal(int32_t batch, const fnn_map* d1, const fnn_map* d2, cons
     }
     FNN_TRY(launch_recip_dedup(L.st, ns, batch, seed_i, seed_j, seed_iter, pairs, n_pairs, s));
     return FNN_OK;
+}
+
+int32_t fnn_reciprocal(int32_t batch, const fnn_map* d1, const fnn_map* d2, const int32_t* seeds, int64_t n_seeds,
+                       const fnn_opts* opts, int32_t* seed_i, int32_t* seed_j, int32_t* seed_iter, int32_t* pairs,
+                       int32_t* n_pairs, void* workspace, size_t workspace_bytes, void* stream) {
+    return reciprocal_impl(batch, d1, d2, seeds, n_seeds, opts, seed_i, seed_j, seed_iter, pairs, n_pairs, workspace,
+                           workspace_bytes, false, stream);
+}
+
+int32_t fnn_reciprocal_static(int32_t batch, const fnn_map* d1, const fnn_map* d2, const int32_t* seeds, int64_t n_seeds,
+                              const fnn_opts* opts, int32_t* seed_i, int32_t* seed_j, int32_t* seed_iter, int32_t* pairs,
+                              int32_t* n_pairs, void* stream) {
+    return reciprocal_impl(batch, d1, d2, seeds, n_seeds, opts, seed_i, seed_j, seed_iter, pairs, n_pairs, nullptr, 0,
+                           true, stream);
 }
 
 int32_t fnn_mutual_dense(int32_t batch, const fnn_map* d1, const fnn_map* d2, const fnn_opts* opts, int32_t* nn12,

@@ -32,7 +32,7 @@ def declared_functions(header="fnn.h"):
 def test_every_declared_symbol_is_exported(lib):
     names = declared_functions()
     assert names == ["fnn_blocked_workspace_bytes", "fnn_mutual_dense", "fnn_nearest", "fnn_nearest_blocked",
-                     "fnn_pairs_to_pixels", "fnn_reciprocal", "fnn_status_string",
+                     "fnn_pairs_to_pixels", "fnn_reciprocal", "fnn_reciprocal_static", "fnn_status_string",
                      "fnn_workspace_bytes", "fnn_workspace_bytes_opts"]
     measure = declared_functions("fnn_measure.h")
     assert measure == ["fnn_measure_ceiling", "fnn_trace_begin", "fnn_trace_end", "fnn_trace_kind_name"]
