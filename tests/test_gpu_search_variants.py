@@ -60,3 +60,46 @@ def test_every_row_group_width_gives_the_same_answers(nq, m, compute, l2, want_g
         else:
             ri, rbest, _ = oracle.nearest(srcs[b][q[b]], cand)
             assert np.array_equal(gi[b], ri) and np.array_equal(gs[b], rbest)
+
+
+@pytest.mark.parametrize("batch,m,compute,kw", [
+    (1, 30011, "f16", {}),              # one pair: chunks shorter than the ring
+    (16, 196608 + 5, "f16", {}),        # the batched shape (four row groups per wave in the ordinary path)
+    (16, 50000, "bf16", {"l2": True}),  # 32-channel rows
+    (4, 40000, "f32", {}),              # fp32 rows
+    (4, 20000, "f16", {"split": True}), # 80-channel rows of the two-term representation (ordinary ring)
+])
+def test_few_live_queries_take_the_streaming_path_with_the_same_answers(batch, m, compute, kw):
+    """A pair with at most 128 live queries is searched by a path of its own (only the 32-query blocks
+    that hold a live query are multiplied, a longer ring of candidate tiles in flight).  Live counts on
+    both sides of every block boundary, mixed within one batch, against the oracle bit for bit; outputs
+    past the live count stay untouched."""
+    n, d, nq = 4096, 24, 160
+    rng = np.random.default_rng(batch * 1000 + m)
+    cand = rng.integers(-8, 9, size=(m, d)).astype(np.float32) / 8
+    tb = dev(cand)
+    srcs = [rng.integers(-8, 9, size=(n, d)).astype(np.float32) / 8 for _ in range(batch)]
+    q = rng.integers(0, n, size=(batch, nq)).astype(np.int32)
+    counts = [1, 31, 32, 33, 63, 64, 65, 96, 97, 127, 128, 129, 160, 3, 0, 106]
+    active = np.array([counts[b % len(counts)] for b in range(batch)], dtype=np.int32)
+    if batch == 1:
+        runs = [np.array([c], dtype=np.int32) for c in (1, 32, 33, 64, 65, 128, 129)]
+    else:
+        runs = [active, np.roll(active, 5)]
+    ts = [dev(x) for x in srcs]
+    for act in runs:
+        out_idx = torch.full((batch, nq), -7, dtype=torch.int32, device="cuda:0")
+        out_score = torch.full((batch, nq), -7.0, dtype=torch.float32, device="cuda:0")
+        fnn.fnn_nearest(ts, [tb] * batch, q_idx=dev(q), nq_active=dev(act), compute=compute,
+                        out_idx=out_idx, out_score=out_score, **kw)
+        torch.cuda.synchronize()
+        gi, gs = host(out_idx), host(out_score)
+        for b in range(batch):
+            k = int(act[b])
+            if kw.get("l2"):
+                ri, rbest, _ = oracle.nearest_l2(srcs[b][q[b, :k]], cand)
+                assert np.array_equal(gi[b, :k], ri) and np.array_equal(-2.0 * gs[b, :k], rbest), (b, k)
+            else:
+                ri, rbest, _ = oracle.nearest(srcs[b][q[b, :k]], cand)
+                assert np.array_equal(gi[b, :k], ri) and np.array_equal(gs[b, :k], rbest), (b, k)
+            assert np.all(gi[b, k:] == -7) and np.all(gs[b, k:] == -7.0), (b, k)
