@@ -202,6 +202,25 @@ bool direct_layout(int32_t batch, const fnn_map* maps, const fnn_opts* opts, int
     return true;
 }
 
+// Caller maps that the fused first searches can read where they are (they round the fp32 rows
+// themselves and write the prepared copy as a by-product): plain fp32 rows of 24 channels that
+// start on 16-byte boundaries, a 16-bit compute format, no options, enough queries.
+bool raw_first_search(int32_t batch, const fnn_map* a, const fnn_map* b, const fnn_opts* opts, int64_t n_queries) {
+    if (opts->flags != 0 || (opts->compute != FNN_F16 && opts->compute != FNN_BF16)) return false;
+    if (!first_search_applies(n_queries)) return false;
+    for (const fnn_map* maps : {a, b})
+        for (int i = 0; i < batch; ++i)
+            if (maps[i].dtype != FNN_F32 || maps[i].d != 24 || maps[i].row_stride % 4 != 0 || maps[i].n <= 0 ||
+                ((uintptr_t)maps[i].data % 16) != 0)
+                return false;
+    return true;
+}
+void fill_raw(RawMaps& r, int32_t batch, const fnn_map* maps) {
+    memset(&r, 0, sizeof(r));
+    for (int i = 0; i < batch; ++i) r.map[i] = (const float*)maps[i].data;
+    r.row_stride = maps[0].row_stride;
+}
+
 // Prepares the maps that are not used in place (skip_a / skip_b) and runs the side jobs.
 hipError_t prep_both(int32_t batch, const fnn_map* a, const fnn_map* b, const MapsLayout& L, int d, const fnn_opts* opts,
                      hipStream_t s, const PrepExtra& extra, bool first_segment_major = false, bool skip_a = false,
@@ -489,7 +508,10 @@ static int32_t reciprocal_impl(int32_t batch, const fnn_map* d1, const fnn_map* 
     int64_t bs1 = L.maps.bstride1, bs2 = L.maps.bstride2;
     const bool direct1 = direct_layout(batch, d1, opts, L.maps.dp, &p1, &bs1);
     const bool direct2 = direct_layout(batch, d2, opts, L.maps.dp, &p2, &bs2);
-    FNN_TRY(prep_both(batch, d1, d2, L.maps, d, opts, s, extra, false, direct1, direct2));
+    // fp32 maps of the paper's shape: no prepare pass; the first forward and the first backward
+    // search read the caller's maps and leave the prepared copies behind for the later searches
+    const bool fused = raw_first_search(batch, d1, d2, opts, n_seeds);
+    FNN_TRY(prep_both(batch, d1, d2, L.maps, d, opts, s, extra, false, direct1 || fused, direct2 || fused));
 
     SearchArgs fwd;  // queries in image 1 -> candidates in image 2
     memset(&fwd, 0, sizeof(fwd));
@@ -520,14 +542,34 @@ static int32_t reciprocal_impl(int32_t batch, const fnn_map* d1, const fnn_map* 
 
     int which = 0;
     fwd.q_idx = L.st.cur_u[which];
-    FNN_TRY(launch_search(fwd, batch, compute, L.maps.dp, s));  // V^0 = NN_2(U^0)
-    FNN_TRY(launch_resolve(fwd, batch, compute, L.maps.dp, nullptr, nullptr, s));
+    if (fused) {
+        FirstSearchArgs first;  // V^0 = NN_2(U^0): queries and candidates still raw; writes the prepared image 2
+        first.s = fwd;
+        first.s.src_rows = (int32_t)n;  // query rows are clamped to the caller's map, which has no padding rows
+        fill_raw(first.raw_tgt, batch, d2);
+        fill_raw(first.raw_src, batch, d1);
+        first.raw_queries = 1;
+        FNN_TRY(launch_search_first(first, batch, compute, s));
+        FNN_TRY(launch_resolve_raw(first, batch, compute, s));
+    } else {
+        FNN_TRY(launch_search(fwd, batch, compute, L.maps.dp, s));  // V^0 = NN_2(U^0)
+        FNN_TRY(launch_resolve(fwd, batch, compute, L.maps.dp, nullptr, nullptr, s));
+    }
     if (opts->max_iter == 0) {
         FNN_TRY(launch_recip_step(L.st, which, ns, batch, 0, 2, seed_i, seed_j, seed_iter, s));
     }
     for (int t = 0; t < opts->max_iter; ++t) {
         const bool last = (t == opts->max_iter - 1);
-        FNN_TRY(launch_search(bwd, batch, compute, L.maps.dp, s));  // U^{t+1} = NN_1(V^t)
+        if (fused && t == 0) {
+            FirstSearchArgs first;  // U^1 = NN_1(V^0): queries from the prepared image 2; writes the prepared image 1
+            first.s = bwd;
+            fill_raw(first.raw_tgt, batch, d1);
+            memset(&first.raw_src, 0, sizeof(first.raw_src));
+            first.raw_queries = 0;
+            FNN_TRY(launch_search_first(first, batch, compute, s));
+        } else {
+            FNN_TRY(launch_search(bwd, batch, compute, L.maps.dp, s));  // U^{t+1} = NN_1(V^t)
+        }
         FNN_TRY(launch_resolve(bwd, batch, compute, L.maps.dp, nullptr, nullptr, s));
         FNN_TRY(launch_recip_step(L.st, which, ns, batch, t, last ? 1 : 0, seed_i, seed_j, seed_iter, s));
         if (last) break;

@@ -48,6 +48,26 @@ __device__ __forceinline__ u64 shfl_xor_u64(u64 v, int mask) {
 }
 
 // ---------------------------------------------------------------------------------------
+// Rounding of an fp32 descriptor value to the 16-bit compute formats (round to nearest even;
+// finite inputs), the cast of Algorithm 3 ("HybridCast").  Every place that rounds uses these.
+// ---------------------------------------------------------------------------------------
+__device__ __forceinline__ uint16_t float_to_bf16_rne(float f) {
+    uint32_t u = __float_as_uint(f);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+__device__ __forceinline__ uint16_t float_to_f16_rne(float f) {
+    _Float16 hf = (_Float16)f;  // v_cvt_f16_f32 rounds to nearest even
+    return __builtin_bit_cast(uint16_t, hf);
+}
+// two values rounded to compute format CT (CT_F16 or CT_BF16) in one 32-bit word, `lo` in the low half
+template <int CT>
+__device__ __forceinline__ uint32_t round_pair(float lo, float hi) {
+    if constexpr (CT == CT_F16) return (uint32_t)float_to_f16_rne(lo) | ((uint32_t)float_to_f16_rne(hi) << 16);
+    else return (uint32_t)float_to_bf16_rne(lo) | ((uint32_t)float_to_bf16_rne(hi) << 16);
+}
+
+// ---------------------------------------------------------------------------------------
 // Matrix-core fragments.  A prepared map stores DP elements per pixel (zero padded).  In a
 // 32-pixel tile lane (c = lane & 31, h = lane >> 5) owns pixel c and a fixed half of its
 // channels (the contiguous half [h*DP/2, (h+1)*DP/2) in the generic layout), for the
@@ -134,6 +154,37 @@ struct OpsHalf24 {
         f.lo = *reinterpret_cast<const uint4*>(tile + (c * 48u + 16u * (uint32_t)h));
         f.hi = *reinterpret_cast<const uint2*>(tile + (c * 48u + 32u + 8u * (uint32_t)h));
         return f;
+    }
+
+    // The 12 fp32 values of an unprepared row that lane half h's fragment is made of (channels
+    // 8h..8h+7 and 16+4h..16+4h+3), and the fragment they round to: bit for bit what the
+    // prepare pass would have stored.  `row` must be 16-byte aligned.
+    struct Raw {
+        float4 a, b, c;
+    };
+    static __device__ __forceinline__ Raw load_raw(const float* row, int h) {
+        Raw r;
+        r.a = *reinterpret_cast<const float4*>(row + 8 * h);
+        r.b = *reinterpret_cast<const float4*>(row + 8 * h + 4);
+        r.c = *reinterpret_cast<const float4*>(row + 16 + 4 * h);
+        return r;
+    }
+    static __device__ __forceinline__ Raw zero_raw() {
+        Raw r;
+        r.a = r.b = r.c = make_float4(0.f, 0.f, 0.f, 0.f);
+        return r;
+    }
+    static __device__ __forceinline__ Frag round_raw(const Raw& r) {
+        Frag f;
+        f.lo = make_uint4(round_pair<CT>(r.a.x, r.a.y), round_pair<CT>(r.a.z, r.a.w), round_pair<CT>(r.b.x, r.b.y),
+                          round_pair<CT>(r.b.z, r.b.w));
+        f.hi = make_uint2(round_pair<CT>(r.c.x, r.c.y), round_pair<CT>(r.c.z, r.c.w));
+        return f;
+    }
+    // lane (c, h)'s fragment into row c of a prepared 32-pixel tile (the layout load_tile reads)
+    static __device__ __forceinline__ void store_tile(char* tile, uint32_t c, int h, const Frag& f) {
+        *reinterpret_cast<uint4*>(tile + (c * 48u + 16u * (uint32_t)h)) = f.lo;
+        *reinterpret_cast<uint2*>(tile + (c * 48u + 32u + 8u * (uint32_t)h)) = f.hi;
     }
 
     static __device__ __forceinline__ f32x16 mma(const Frag& a, const Frag& b) {

@@ -111,6 +111,26 @@ struct SearchArgs {
 };
 // Pass 1: out_keys receive (best score, tile of 32 candidates holding it).
 hipError_t launch_search(const SearchArgs& a, int batch, int compute, int dp, hipStream_t s);
+
+// The first searches of a call whose maps are still the caller's fp32 arrays (24 channels, a
+// 16-bit compute format, every query live): the candidates are read from the caller's map,
+// rounded on the way, staged through LDS once per workgroup, and written to the prepared map
+// `s.tgt` as a by-product, so no separate prepare pass over that map is needed.
+struct RawMaps {
+    const float* map[FNN_MAX_BATCH];  // caller's map of every pair (16-byte aligned rows)
+    int64_t row_stride;               // floats per row (a multiple of 4)
+};
+struct FirstSearchArgs {
+    SearchArgs s;      // s.tgt: prepared candidate map to WRITE; s.nq_active is ignored (all nq queries are live)
+    RawMaps raw_tgt;   // candidates
+    RawMaps raw_src;   // queries, when raw_queries != 0 (else they are rows of the prepared map s.src)
+    int32_t raw_queries;
+};
+// true if this shape should take the fused first search (enough queries to fill the workgroups)
+bool first_search_applies(int64_t nq);
+hipError_t launch_search_first(const FirstSearchArgs& a, int batch, int compute, hipStream_t s);
+// launch_resolve with the queries still in the caller's fp32 map
+hipError_t launch_resolve_raw(const FirstSearchArgs& a, int batch, int compute, hipStream_t s);
 // Pass 2: out_keys become (best score, lowest candidate index); optionally also stored to
 // out_idx / out_score (either may be NULL).  Queries without any candidate get -1 / -inf.
 hipError_t launch_resolve(const SearchArgs& a, int batch, int compute, int dp, int32_t* out_idx, float* out_score,

@@ -18,17 +18,6 @@ __device__ __forceinline__ float load_as_float(const void* base, int64_t idx, in
     return __uint_as_float((uint32_t)raw << 16);
 }
 
-__device__ __forceinline__ uint16_t float_to_bf16_rne(float f) {
-    uint32_t u = __float_as_uint(f);
-    u += 0x7FFFu + ((u >> 16) & 1u);
-    return (uint16_t)(u >> 16);
-}
-
-__device__ __forceinline__ uint16_t float_to_f16_rne(float f) {
-    _Float16 hf = (_Float16)f;  // v_cvt_f16_f32 rounds to nearest even
-    return __builtin_bit_cast(uint16_t, hf);
-}
-
 // Euclidean norm of one source descriptor as FNN_FLAG_NORMALIZE defines it: squares and
 // sums rounded separately (no fused multiply-add), channels in ascending order.
 __device__ __forceinline__ float descriptor_norm(const void* src, int64_t first, int d, int dtype) {

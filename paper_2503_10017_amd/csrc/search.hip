@@ -14,6 +14,8 @@
 // chunks, one wave takes one (row group, chunk) unit -- every candidate tile it loads meets
 // G groups of R query blocks, a group past the live queries is skipped -- and merges its
 // result into the packed keys with a 64-bit atomic max (score first, lowest index on ties).
+#include <type_traits>
+
 #include "fnn_device.hpp"
 #include "fnn_kernels.hpp"
 #include "trace.hpp"
@@ -239,13 +241,163 @@ void search_kernel(SearchArgs a) {
     }
 }
 
+// ---- the first searches of a call, on maps that are not prepared yet -----------------------
+// Same arithmetic and same keys as search_kernel, for the case "every query live, candidates
+// still in the caller's fp32 map" (the first forward and the first backward search of the
+// FastNN iteration).  A workgroup's four waves take four row groups of ONE candidate chunk:
+// each turn every wave fetches one 32-pixel tile of the caller's map, rounds it to the compute
+// format in registers (the cast of Algorithm 3), puts the fragment into the workgroup's LDS
+// ring and -- first row-group quad only -- stores it to the prepared map; after a barrier all
+// four waves read the four staged tiles from LDS and multiply them with their resident query
+// blocks.  The map is thus read once per quad instead of once per wave, the raw tiles of the
+// next two turns are always in flight, and the separate prepare pass over the map disappears.
+constexpr int FIRST_G = 3;        // groups of R query blocks per wave: 3072 queries = 8 row groups = 2 quads
+constexpr int FIRST_TURN = SEARCH_WAVES;  // tiles staged per turn (one per wave)
+constexpr int FIRST_AHEAD = 2;    // turns whose raw tiles are in flight
+
+template <int CT>
+__device__ __forceinline__ typename Ops<CT, 24>::Raw first_raw_tile(const FirstSearchArgs& fa, int b, int t, int t1, int c, int h) {
+    using O = Ops<CT, 24>;
+    const int64_t pixel = (int64_t)t * 32 + c;
+    if (t < t1 && pixel < fa.s.m) return O::load_raw(fa.raw_tgt.map[b] + pixel * fa.raw_tgt.row_stride, h);
+    return O::zero_raw();  // padding rows of the prepared map are zero
+}
+
+template <int CT, int G>
+__global__ __launch_bounds__(SEARCH_WAVES * 64) __attribute__((amdgpu_waves_per_eu(2)))
+void search_first_kernel(FirstSearchArgs fa) {
+    using O = Ops<CT, 24>;
+    using Frag = typename O::Frag;
+    using Raw = typename O::Raw;
+    constexpr int R = SEARCH_R;
+    const SearchArgs& a = fa.s;
+    __shared__ uint4 stage_lo[2][FIRST_TURN][64];
+    __shared__ uint2 stage_hi[2][FIRST_TURN][64];
+    const int lane = threadIdx.x & 63, c = lane & 31, h = lane >> 5;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    // one XCD owns a contiguous run of (pair, unit) work, see search_kernel
+    const int n_wgs = gridDim.x * gridDim.y;
+    int wg = blockIdx.y * gridDim.x + blockIdx.x;
+    if ((n_wgs & 7) == 0) wg = (wg & 7) * (n_wgs >> 3) + (wg >> 3);
+    const int b = wg / gridDim.x;
+    const int wgi = wg % gridDim.x;
+    const int n_act = a.nq;
+    if (n_act <= 0 || a.m_tiles <= 0) return;
+
+    const int row_groups = (n_act + 32 * R * G - 1) / (32 * R * G);
+    const int quads = (row_groups + SEARCH_WAVES - 1) / SEARCH_WAVES;
+    int chunks = max(1, (int)gridDim.x / quads);
+    int tiles_per_chunk = (a.m_tiles + chunks - 1) / chunks;
+    tiles_per_chunk = (tiles_per_chunk + FIRST_TURN - 1) / FIRST_TURN * FIRST_TURN;
+    chunks = (a.m_tiles + tiles_per_chunk - 1) / tiles_per_chunk;
+
+    const char* src = a.src + (int64_t)b * a.src_bstride;
+    char* tgt = const_cast<char*>(a.tgt) + (int64_t)b * a.tgt_bstride;
+    const int64_t qbase = (int64_t)b * a.nq;
+    const float ninf = -__builtin_inff();
+
+    const int units = quads * chunks;
+    for (int unit = wgi; unit < units; unit += gridDim.x) {  // uniform in the workgroup
+        const int chunk = unit / quads, quad = unit % quads;
+        const int slot0 = (quad * SEARCH_WAVES + wave) * 32 * R * G;
+        const int t0 = chunk * tiles_per_chunk;
+        const int t1 = min(t0 + tiles_per_chunk, a.m_tiles);
+        const int n_turns = (t1 - t0 + FIRST_TURN - 1) / FIRST_TURN;
+
+        static_assert(FIRST_AHEAD == 2, "the turn loop below is unrolled by the two ring slots");
+        Raw raw[FIRST_AHEAD];
+#pragma unroll
+        for (int p = 0; p < FIRST_AHEAD; ++p) raw[p] = first_raw_tile<CT>(fa, b, t0 + p * FIRST_TURN + wave, t1, c, h);
+
+        Frag q[G][R];
+        float best[G][R];
+        int best_tile[G][R];
+        bool live[G];
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+            live[g] = slot0 + g * 32 * R < n_act;  // uniform in the wave
+#pragma unroll
+            for (int r = 0; r < R; ++r) {
+                const int slot = slot0 + (g * R + r) * 32 + c;
+                const int64_t row = slot < n_act ? query_row(a, qbase, slot) : 0;
+                if (fa.raw_queries) q[g][r] = O::round_raw(O::load_raw(fa.raw_src.map[b] + row * fa.raw_src.row_stride, h));
+                else q[g][r] = O::load(src + row * O::ROW_BYTES, h);
+                best[g][r] = ninf;
+                best_tile[g][r] = 0x7FFFFFFF;
+            }
+        }
+
+        // one turn: stage my tile of the turn, then multiply the four staged tiles
+        auto turn = [&](int k, auto slot_tag) {
+            constexpr int SLOT = decltype(slot_tag)::value;
+            const int mine = t0 + k * FIRST_TURN + wave;
+            const Frag f = O::round_raw(raw[SLOT]);
+            stage_lo[SLOT][wave][lane] = f.lo;
+            stage_hi[SLOT][wave][lane] = f.hi;
+            if (quad == 0 && mine < t1) O::store_tile(tgt + (int64_t)mine * (32 * O::ROW_BYTES), c, h, f);
+            raw[SLOT] = first_raw_tile<CT>(fa, b, mine + FIRST_AHEAD * FIRST_TURN, t1, c, h);
+            __syncthreads();
+#pragma unroll
+            for (int j = 0; j < FIRST_TURN; ++j) {
+                const int t = t0 + k * FIRST_TURN + j;
+                if (t < t1) {  // uniform
+                    Frag cur;
+                    cur.lo = stage_lo[SLOT][j][lane];
+                    cur.hi = stage_hi[SLOT][j][lane];
+#pragma unroll
+                    for (int g = 0; g < G; ++g) {
+                        if (live[g]) {
+                            f32x16 acc[R];
+#pragma unroll
+                            for (int r = 0; r < R; ++r) acc[r] = O::mma(cur, q[g][r]);
+                            if (t * 32 + 32 > a.m) {  // only the last tile of the map can be partial
+                                const int bound = a.m - t * 32 - 4 * h;
+#pragma unroll
+                                for (int r = 0; r < R; ++r)
+#pragma unroll
+                                    for (int v = 0; v < 16; ++v)
+                                        if (tile_row(v, 0) >= bound) acc[r][v] = ninf;
+                            }
+#pragma unroll
+                            for (int r = 0; r < R; ++r) {
+                                const float top = fold16(best[g][r], acc[r]);
+                                if (top > best[g][r]) best_tile[g][r] = t;
+                                best[g][r] = top;
+                            }
+                        }
+                    }
+                }
+            }
+        };
+        for (int k = 0; k < n_turns; k += 2) {
+            turn(k, std::integral_constant<int, 0>{});
+            if (k + 1 < n_turns) turn(k + 1, std::integral_constant<int, 1>{});  // uniform
+        }
+
+#pragma unroll
+        for (int g = 0; g < G; ++g)
+#pragma unroll
+            for (int r = 0; r < R; ++r) {
+                const float ob = __shfl_xor(best[g][r], 32);
+                const int ot = __shfl_xor(best_tile[g][r], 32);
+                if (ob > best[g][r] || (ob == best[g][r] && ot < best_tile[g][r])) {
+                    best[g][r] = ob;
+                    best_tile[g][r] = ot;
+                }
+                const int slot = slot0 + (g * R + r) * 32 + c;
+                if (h == 0 && slot < n_act) atomicMax(&a.out_keys[qbase + slot], pack_key(best[g][r], best_tile[g][r]));
+            }
+        __syncthreads();  // the next unit's first turn reuses ring slot 0
+    }
+}
+
 // Pass 2: one wave per query recomputes the 32 scores of the winning tile with the same
 // matrix instruction (the query replicated into every column, so each score has the bits
 // pass 1 saw) and picks the lowest candidate that attains the maximum.  The key is
 // rewritten with the candidate index; optionally index and score are stored as well.
-template <int CT, int DP>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2)))
-void resolve_kernel(SearchArgs a, int32_t* out_idx, float* out_score) {
+// load_query(b, row, h) supplies the query fragment.
+template <int CT, int DP, typename LoadQuery>
+__device__ __forceinline__ void resolve_body(const SearchArgs& a, int32_t* out_idx, float* out_score, LoadQuery load_query) {
     using O = Ops<CT, DP>;
     using Frag = typename O::Frag;
     const int lane = threadIdx.x & 63, c = lane & 31, h = lane >> 5;
@@ -254,7 +406,6 @@ void resolve_kernel(SearchArgs a, int32_t* out_idx, float* out_score) {
     const int b = blockIdx.y;
     int n_act = a.nq;
     if (a.nq_active) n_act = min(max(a.nq_active[b], 0), a.nq);
-    const char* src = a.src + (int64_t)b * a.src_bstride;
     const char* tgt = a.tgt + (int64_t)b * a.tgt_bstride;
     const int64_t qbase = (int64_t)b * a.nq;
     const float ninf = -__builtin_inff();
@@ -265,7 +416,7 @@ void resolve_kernel(SearchArgs a, int32_t* out_idx, float* out_score) {
         float score = ninf;
         if (key != 0) {
             const int tile = min(key_index(key), a.m_tiles - 1);
-            const Frag qf = O::load(src + query_row(a, qbase, slot) * O::ROW_BYTES, h);
+            const Frag qf = load_query(b, query_row(a, qbase, slot), h);
             const Frag cand = O::load(tgt + ((int64_t)tile * 32 + c) * O::ROW_BYTES, h);
             f32x16 acc = O::mma(cand, qf);
             if (tile * 32 + 32 > a.m) {
@@ -289,6 +440,26 @@ void resolve_kernel(SearchArgs a, int32_t* out_idx, float* out_score) {
             if (out_score) out_score[qbase + slot] = score;
         }
     }
+}
+
+template <int CT, int DP>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2)))
+void resolve_kernel(SearchArgs a, int32_t* out_idx, float* out_score) {
+    using O = Ops<CT, DP>;
+    resolve_body<CT, DP>(a, out_idx, out_score, [&](int b, int64_t row, int h) {
+        return O::load(a.src + (int64_t)b * a.src_bstride + row * O::ROW_BYTES, h);
+    });
+}
+
+// The same with the queries still in the caller's fp32 map (rounded on the way, like the
+// fused first search rounds them).
+template <int CT>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2)))
+void resolve_raw_kernel(FirstSearchArgs fa) {
+    using O = Ops<CT, 24>;
+    resolve_body<CT, 24>(fa.s, nullptr, nullptr, [&](int b, int64_t row, int h) {
+        return O::round_raw(O::load_raw(fa.raw_src.map[b] + row * fa.raw_src.row_stride, h));
+    });
 }
 
 // One resident wave per hardware slot: the grid is exactly what the chip holds at once
@@ -381,6 +552,51 @@ hipError_t launch_search(const SearchArgs& a, int batch, int compute, int dp, hi
         if (dp == 24) return launch_search_t<CT_F32, 24>(a, batch, s);
         if (dp == 32) return launch_search_t<CT_F32, 32>(a, batch, s);
     }
+    return hipErrorInvalidValue;
+}
+
+// ---- fused first search: launch shape ------------------------------------------------------
+bool first_search_applies(int64_t nq) {
+    // at least one full quad of row groups, so that the four waves of a workgroup all have queries
+    return nq >= (int64_t)SEARCH_WAVES * 32 * SEARCH_R * FIRST_G;
+}
+
+template <int CT>
+static hipError_t launch_search_first_t(const FirstSearchArgs& a, int batch, hipStream_t s) {
+    static DeviceCache resident_wgs;
+    const long long resident = resident_wgs.get([](int dev) -> long long {
+        int per_cu = 0;
+        hipDeviceProp_t prop;
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, search_first_kernel<CT, FIRST_G>, SEARCH_WAVES * 64, 0) != hipSuccess ||
+            hipGetDeviceProperties(&prop, dev) != hipSuccess)
+            return -1;
+        return (long long)(per_cu > 0 ? per_cu : 1) * prop.multiProcessorCount;
+    });
+    if (resident <= 0) return hipErrorUnknown;
+    int wgs = (int)resident / batch;
+    if (wgs >= 8) wgs &= ~7;
+    if (wgs < 1) wgs = 1;
+    const int row_groups = (a.s.nq + 32 * SEARCH_R * FIRST_G - 1) / (32 * SEARCH_R * FIRST_G);
+    const int quads = (row_groups + SEARCH_WAVES - 1) / SEARCH_WAVES;
+    const int64_t max_units = (int64_t)quads * ((a.s.m_tiles + FIRST_TURN - 1) / FIRST_TURN);
+    if (max_units < wgs) wgs = (int)(max_units > 0 ? max_units : 1);
+    return launch_detail(TK_SEARCH, 100 + FIRST_G, search_first_kernel<CT, FIRST_G>, dim3(wgs, batch), dim3(SEARCH_WAVES * 64), 0, s, a);
+}
+
+hipError_t launch_search_first(const FirstSearchArgs& a, int batch, int compute, hipStream_t s) {
+    if (a.s.nq <= 0 || batch <= 0) return hipSuccess;
+    if (compute == FNN_F16) return launch_search_first_t<CT_F16>(a, batch, s);
+    if (compute == FNN_BF16) return launch_search_first_t<CT_BF16>(a, batch, s);
+    return hipErrorInvalidValue;
+}
+
+hipError_t launch_resolve_raw(const FirstSearchArgs& a, int batch, int compute, hipStream_t s) {
+    if (a.s.nq <= 0 || batch <= 0) return hipSuccess;
+    int wgs = (a.s.nq + 3) / 4;
+    const int cap = 2048 / batch > 64 ? 2048 / batch : 64;
+    if (wgs > cap) wgs = cap;
+    if (compute == FNN_F16) return launch(TK_RESOLVE, resolve_raw_kernel<CT_F16>, dim3(wgs, batch), dim3(256), 0, s, a);
+    if (compute == FNN_BF16) return launch(TK_RESOLVE, resolve_raw_kernel<CT_BF16>, dim3(wgs, batch), dim3(256), 0, s, a);
     return hipErrorInvalidValue;
 }
 
