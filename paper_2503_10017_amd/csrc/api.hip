@@ -511,6 +511,8 @@ static int32_t reciprocal_impl(int32_t batch, const fnn_map* d1, const fnn_map* 
     // fp32 maps of the paper's shape: no prepare pass; the first forward and the first backward
     // search read the caller's maps and leave the prepared copies behind for the later searches
     const bool fused = raw_first_search(batch, d1, d2, opts, n_seeds);
+    // the same LDS-staged kernel serves the first two searches on prepared 24-channel maps
+    const bool staged = fused || (L.maps.dp == 24 && opts->compute != FNN_F32 && first_search_applies(n_seeds));
     FNN_TRY(prep_both(batch, d1, d2, L.maps, d, opts, s, extra, false, direct1 || fused, direct2 || fused));
 
     SearchArgs fwd;  // queries in image 1 -> candidates in image 2
@@ -551,6 +553,12 @@ static int32_t reciprocal_impl(int32_t batch, const fnn_map* d1, const fnn_map* 
         first.raw_queries = 1;
         FNN_TRY(launch_search_first(first, batch, compute, s));
         FNN_TRY(launch_resolve_raw(first, batch, compute, s));
+    } else if (staged) {
+        FirstSearchArgs first;
+        memset(&first, 0, sizeof(first));
+        first.s = fwd;
+        FNN_TRY(launch_search_first(first, batch, compute, s));
+        FNN_TRY(launch_resolve(fwd, batch, compute, L.maps.dp, nullptr, nullptr, s));
     } else {
         FNN_TRY(launch_search(fwd, batch, compute, L.maps.dp, s));  // V^0 = NN_2(U^0)
         FNN_TRY(launch_resolve(fwd, batch, compute, L.maps.dp, nullptr, nullptr, s));
@@ -560,12 +568,11 @@ static int32_t reciprocal_impl(int32_t batch, const fnn_map* d1, const fnn_map* 
     }
     for (int t = 0; t < opts->max_iter; ++t) {
         const bool last = (t == opts->max_iter - 1);
-        if (fused && t == 0) {
-            FirstSearchArgs first;  // U^1 = NN_1(V^0): queries from the prepared image 2; writes the prepared image 1
+        if (staged && t == 0) {
+            FirstSearchArgs first;  // U^1 = NN_1(V^0): queries from the prepared image 2; if raw, writes the prepared image 1
+            memset(&first, 0, sizeof(first));
             first.s = bwd;
-            fill_raw(first.raw_tgt, batch, d1);
-            memset(&first.raw_src, 0, sizeof(first.raw_src));
-            first.raw_queries = 0;
+            if (fused) fill_raw(first.raw_tgt, batch, d1);
             FNN_TRY(launch_search_first(first, batch, compute, s));
         } else {
             FNN_TRY(launch_search(bwd, batch, compute, L.maps.dp, s));  // U^{t+1} = NN_1(V^t)

@@ -255,20 +255,33 @@ constexpr int FIRST_G = 3;        // groups of R query blocks per wave: 3072 que
 constexpr int FIRST_TURN = SEARCH_WAVES;  // tiles staged per turn (one per wave)
 constexpr int FIRST_AHEAD = 2;    // turns whose raw tiles are in flight
 
-template <int CT>
-__device__ __forceinline__ typename Ops<CT, 24>::Raw first_raw_tile(const FirstSearchArgs& fa, int b, int t, int t1, int c, int h) {
+// A candidate tile on its way to the LDS ring: the 12 fp32 values of the caller's row (RAWT), or
+// the fragment of an already prepared map.
+template <int CT, bool RAWT>
+struct FirstTile {
     using O = Ops<CT, 24>;
-    const int64_t pixel = (int64_t)t * 32 + c;
-    if (t < t1 && pixel < fa.s.m) return O::load_raw(fa.raw_tgt.map[b] + pixel * fa.raw_tgt.row_stride, h);
-    return O::zero_raw();  // padding rows of the prepared map are zero
-}
+    using Pending = std::conditional_t<RAWT, typename O::Raw, typename O::Frag>;
+    static __device__ __forceinline__ Pending fetch(const FirstSearchArgs& fa, const char* tgt, int b, int t, int t1, int c, int h) {
+        if constexpr (RAWT) {
+            const int64_t pixel = (int64_t)t * 32 + c;
+            if (t < t1 && pixel < fa.s.m) return O::load_raw(fa.raw_tgt.map[b] + pixel * fa.raw_tgt.row_stride, h);
+            return O::zero_raw();  // padding rows of the prepared map are zero
+        } else {
+            return O::load_tile(tgt + (int64_t)min(t, t1 - 1) * (32 * O::ROW_BYTES), c, h);
+        }
+    }
+    static __device__ __forceinline__ typename O::Frag fragment(const Pending& p) {
+        if constexpr (RAWT) return O::round_raw(p);
+        else return p;
+    }
+};
 
-template <int CT, int G>
+template <int CT, int G, bool RAWT>
 __global__ __launch_bounds__(SEARCH_WAVES * 64) __attribute__((amdgpu_waves_per_eu(2)))
 void search_first_kernel(FirstSearchArgs fa) {
     using O = Ops<CT, 24>;
     using Frag = typename O::Frag;
-    using Raw = typename O::Raw;
+    using Tile = FirstTile<CT, RAWT>;
     constexpr int R = SEARCH_R;
     const SearchArgs& a = fa.s;
     __shared__ uint4 stage_lo[2][FIRST_TURN][64];
@@ -305,9 +318,9 @@ void search_first_kernel(FirstSearchArgs fa) {
         const int n_turns = (t1 - t0 + FIRST_TURN - 1) / FIRST_TURN;
 
         static_assert(FIRST_AHEAD == 2, "the turn loop below is unrolled by the two ring slots");
-        Raw raw[FIRST_AHEAD];
+        typename Tile::Pending raw[FIRST_AHEAD];
 #pragma unroll
-        for (int p = 0; p < FIRST_AHEAD; ++p) raw[p] = first_raw_tile<CT>(fa, b, t0 + p * FIRST_TURN + wave, t1, c, h);
+        for (int p = 0; p < FIRST_AHEAD; ++p) raw[p] = Tile::fetch(fa, tgt, b, t0 + p * FIRST_TURN + wave, t1, c, h);
 
         Frag q[G][R];
         float best[G][R];
@@ -331,11 +344,11 @@ void search_first_kernel(FirstSearchArgs fa) {
         auto turn = [&](int k, auto slot_tag) {
             constexpr int SLOT = decltype(slot_tag)::value;
             const int mine = t0 + k * FIRST_TURN + wave;
-            const Frag f = O::round_raw(raw[SLOT]);
+            const Frag f = Tile::fragment(raw[SLOT]);
             stage_lo[SLOT][wave][lane] = f.lo;
             stage_hi[SLOT][wave][lane] = f.hi;
-            if (quad == 0 && mine < t1) O::store_tile(tgt + (int64_t)mine * (32 * O::ROW_BYTES), c, h, f);
-            raw[SLOT] = first_raw_tile<CT>(fa, b, mine + FIRST_AHEAD * FIRST_TURN, t1, c, h);
+            if (RAWT && quad == 0 && mine < t1) O::store_tile(tgt + (int64_t)mine * (32 * O::ROW_BYTES), c, h, f);
+            raw[SLOT] = Tile::fetch(fa, tgt, b, mine + FIRST_AHEAD * FIRST_TURN, t1, c, h);
             __syncthreads();
 #pragma unroll
             for (int j = 0; j < FIRST_TURN; ++j) {
@@ -561,13 +574,13 @@ bool first_search_applies(int64_t nq) {
     return nq >= (int64_t)SEARCH_WAVES * 32 * SEARCH_R * FIRST_G;
 }
 
-template <int CT>
+template <int CT, bool RAWT>
 static hipError_t launch_search_first_t(const FirstSearchArgs& a, int batch, hipStream_t s) {
     static DeviceCache resident_wgs;
     const long long resident = resident_wgs.get([](int dev) -> long long {
         int per_cu = 0;
         hipDeviceProp_t prop;
-        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, search_first_kernel<CT, FIRST_G>, SEARCH_WAVES * 64, 0) != hipSuccess ||
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, search_first_kernel<CT, FIRST_G, RAWT>, SEARCH_WAVES * 64, 0) != hipSuccess ||
             hipGetDeviceProperties(&prop, dev) != hipSuccess)
             return -1;
         return (long long)(per_cu > 0 ? per_cu : 1) * prop.multiProcessorCount;
@@ -580,13 +593,14 @@ static hipError_t launch_search_first_t(const FirstSearchArgs& a, int batch, hip
     const int quads = (row_groups + SEARCH_WAVES - 1) / SEARCH_WAVES;
     const int64_t max_units = (int64_t)quads * ((a.s.m_tiles + FIRST_TURN - 1) / FIRST_TURN);
     if (max_units < wgs) wgs = (int)(max_units > 0 ? max_units : 1);
-    return launch_detail(TK_SEARCH, 100 + FIRST_G, search_first_kernel<CT, FIRST_G>, dim3(wgs, batch), dim3(SEARCH_WAVES * 64), 0, s, a);
+    return launch_detail(TK_SEARCH, 100 + FIRST_G, search_first_kernel<CT, FIRST_G, RAWT>, dim3(wgs, batch), dim3(SEARCH_WAVES * 64), 0, s, a);
 }
 
 hipError_t launch_search_first(const FirstSearchArgs& a, int batch, int compute, hipStream_t s) {
     if (a.s.nq <= 0 || batch <= 0) return hipSuccess;
-    if (compute == FNN_F16) return launch_search_first_t<CT_F16>(a, batch, s);
-    if (compute == FNN_BF16) return launch_search_first_t<CT_BF16>(a, batch, s);
+    const bool raw = a.raw_tgt.map[0] != nullptr;  // else the candidates are the prepared map s.tgt itself
+    if (compute == FNN_F16) return raw ? launch_search_first_t<CT_F16, true>(a, batch, s) : launch_search_first_t<CT_F16, false>(a, batch, s);
+    if (compute == FNN_BF16) return raw ? launch_search_first_t<CT_BF16, true>(a, batch, s) : launch_search_first_t<CT_BF16, false>(a, batch, s);
     return hipErrorInvalidValue;
 }
 

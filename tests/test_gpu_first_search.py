@@ -1,0 +1,92 @@
+"""The first forward and the first backward search of fnn_reciprocal on 24-channel maps with a 16-bit
+compute format and at least 1536 seeds run in a kernel of their own: candidate tiles are staged through
+LDS once per workgroup, and fp32 maps are read where the caller holds them (rounded on the way, the
+prepared copy written as a by-product, no prepare pass).  Exactly representable maps: everything must
+match the oracle bit for bit, whichever path a call takes, and the trace says which one it took."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2503_10017_amd as fnn
+from gpu_helpers import check_reciprocal_exact, dev, host
+
+pytestmark = pytest.mark.gpu
+
+STAGED = 103   # trace detail of the LDS-staged first-search kernel (100 + groups of query blocks per wave)
+
+
+def traced_reciprocal(t1, t2, seeds, compute):
+    fnn.fnn_trace_begin(128)
+    try:
+        out = fnn.fnn_reciprocal(t1, t2, seeds, max_iter=10, compute=compute)
+        torch.cuda.synchronize()
+    finally:
+        trace = fnn.fnn_trace_end(128, details=True)
+    searches = [detail for name, _, detail in trace if name == "search_kernel"]
+    prep_ms = [ms for name, ms, _ in trace if name == "prep_kernel"]
+    return {k: host(v) for k, v in out.items()}, searches, prep_ms
+
+
+def exact(rng, rows, stride=24):
+    wide = np.zeros((rows, stride), dtype=np.float32)
+    wide[:, :24] = rng.integers(-8, 9, size=(rows, 24)).astype(np.float32) / 8
+    wide[:, 24:] = 5.0   # junk between the rows must be ignored
+    return wide
+
+
+@pytest.mark.parametrize("compute", ["f16", "bf16"])
+@pytest.mark.parametrize("n,m,n_seeds,batch,stride", [
+    (5000, 7013, 1600, 2, 24),     # partial tiles on both sides; 5 row groups: the second quad has three idle waves
+    (4096, 4128, 3072, 1, 28),     # rows 28 floats apart
+    (9001, 3333, 1536, 3, 24),     # exactly one quad
+])
+def test_fp32_maps_are_searched_where_they_are(compute, n, m, n_seeds, batch, stride):
+    rng = np.random.default_rng(n + m)
+    a = [exact(rng, n, stride) for _ in range(batch)]
+    b = [exact(rng, m, stride) for _ in range(batch)]
+    seeds = rng.integers(0, n, size=(batch, n_seeds)).astype(np.int32)
+    t1 = [dev(x)[:, :24] for x in a]
+    t2 = [dev(x)[:, :24] for x in b]
+    got, searches, _ = traced_reciprocal(t1, t2, dev(seeds), compute)
+    assert searches[:2] == [STAGED, STAGED] and STAGED not in searches[2:]
+    for p in range(batch):
+        check_reciprocal_exact(got, p, oracle.reciprocal(a[p][:, :24], b[p][:, :24], seeds[p], 10))
+
+
+def test_prepared_maps_take_the_staged_kernel_too_and_small_seed_sets_do_not():
+    rng = np.random.default_rng(77)
+    n, m = 4096, 6400
+    a, b = exact(rng, n), exact(rng, m)
+    seeds = rng.integers(0, n, size=(1, 2000)).astype(np.int32)
+    ref = oracle.reciprocal(a, b, seeds[0], 10)
+    # stored in the compute format: read in place, no copy, staged first searches
+    got, searches, _ = traced_reciprocal(dev(a).half(), dev(b).half(), dev(seeds), "f16")
+    assert searches[:2] == [STAGED, STAGED]
+    check_reciprocal_exact(got, 0, ref)
+    # fp16 storage with padded rows: prepare pass, then the staged kernel on the prepared copy
+    wide_a = torch.zeros((n, 40), dtype=torch.float16, device="cuda:0")
+    wide_b = torch.zeros((m, 40), dtype=torch.float16, device="cuda:0")
+    wide_a[:, :24], wide_b[:, :24] = dev(a).half(), dev(b).half()
+    got, searches, _ = traced_reciprocal(wide_a[:, :24], wide_b[:, :24], dev(seeds), "f16")
+    assert searches[:2] == [STAGED, STAGED]
+    check_reciprocal_exact(got, 0, ref)
+    # fewer seeds than one quad of row groups: the ordinary search kernel
+    few = seeds[:, :1535]
+    got, searches, _ = traced_reciprocal(dev(a), dev(b), dev(few), "f16")
+    assert STAGED not in searches
+    check_reciprocal_exact(got, 0, oracle.reciprocal(a, b, few[0], 10))
+    # fp32 products: the ordinary kernels
+    got, searches, _ = traced_reciprocal(dev(a), dev(b), dev(seeds), "f32")
+    assert STAGED not in searches
+    check_reciprocal_exact(got, 0, ref)
+
+
+def test_misaligned_fp32_rows_fall_back_to_the_prepare_pass():
+    rng = np.random.default_rng(78)
+    n, m = 4096, 4096
+    a, b = exact(rng, n, 25), exact(rng, m, 25)     # rows 25 floats apart: no 16-byte alignment
+    seeds = rng.integers(0, n, size=(1, 1600)).astype(np.int32)
+    got, searches, _ = traced_reciprocal(dev(a)[:, :24], dev(b)[:, :24], dev(seeds), "f16")
+    assert searches[:2] == [STAGED, STAGED]           # the staged kernel, on the copy the prepare pass made
+    check_reciprocal_exact(got, 0, oracle.reciprocal(a[:, :24], b[:, :24], seeds[0], 10))
