@@ -207,7 +207,7 @@ bool direct_layout(int32_t batch, const fnn_map* maps, const fnn_opts* opts, int
 // start on 16-byte boundaries, a 16-bit compute format, no options, enough queries.
 bool raw_first_search(int32_t batch, const fnn_map* a, const fnn_map* b, const fnn_opts* opts, int64_t n_queries) {
     if (opts->flags != 0 || (opts->compute != FNN_F16 && opts->compute != FNN_BF16)) return false;
-    if (!first_search_applies(n_queries)) return false;
+    if (!first_search_applies(n_queries, a[0].n, batch) || !first_search_applies(n_queries, b[0].n, batch)) return false;
     for (const fnn_map* maps : {a, b})
         for (int i = 0; i < batch; ++i)
             if (maps[i].dtype != FNN_F32 || maps[i].d != 24 || maps[i].row_stride % 4 != 0 || maps[i].n <= 0 ||
@@ -512,7 +512,8 @@ static int32_t reciprocal_impl(int32_t batch, const fnn_map* d1, const fnn_map* 
     // search read the caller's maps and leave the prepared copies behind for the later searches
     const bool fused = raw_first_search(batch, d1, d2, opts, n_seeds);
     // the same LDS-staged kernel serves the first two searches on prepared 24-channel maps
-    const bool staged = fused || (L.maps.dp == 24 && opts->compute != FNN_F32 && first_search_applies(n_seeds));
+    const bool staged = fused || (L.maps.dp == 24 && opts->compute != FNN_F32 && first_search_applies(n_seeds, n, batch) &&
+                                  first_search_applies(n_seeds, m, batch));
     FNN_TRY(prep_both(batch, d1, d2, L.maps, d, opts, s, extra, false, direct1 || fused, direct2 || fused));
 
     SearchArgs fwd;  // queries in image 1 -> candidates in image 2

@@ -126,8 +126,9 @@ struct FirstSearchArgs {
     RawMaps raw_src;   // queries, when raw_queries != 0 (else they are rows of the prepared map s.src)
     int32_t raw_queries;
 };
-// true if this shape should take the fused first search (enough queries to fill the workgroups)
-bool first_search_applies(int64_t nq);
+// true if this shape should take the staged first search: enough queries to fill the workgroups'
+// four waves and, with `batch` pairs sharing the device, chunks of m candidates long enough
+bool first_search_applies(int64_t nq, int64_t m, int batch);
 hipError_t launch_search_first(const FirstSearchArgs& a, int batch, int compute, hipStream_t s);
 // launch_resolve with the queries still in the caller's fp32 map
 hipError_t launch_resolve_raw(const FirstSearchArgs& a, int batch, int compute, hipStream_t s);

@@ -254,6 +254,7 @@ void search_kernel(SearchArgs a) {
 constexpr int FIRST_G = 3;        // groups of R query blocks per wave: 3072 queries = 8 row groups = 2 quads
 constexpr int FIRST_TURN = SEARCH_WAVES;  // tiles staged per turn (one per wave)
 constexpr int FIRST_AHEAD = 2;    // turns whose raw tiles are in flight
+constexpr int FIRST_MIN_CHUNK = 32;  // tiles a chunk must hold for the staged kernel to be worth its start-up
 
 // A candidate tile on its way to the LDS ring: the 12 fp32 values of the caller's row (RAWT), or
 // the fragment of an already prepared map.
@@ -569,26 +570,41 @@ hipError_t launch_search(const SearchArgs& a, int batch, int compute, int dp, hi
 }
 
 // ---- fused first search: launch shape ------------------------------------------------------
-bool first_search_applies(int64_t nq) {
-    // at least one full quad of row groups, so that the four waves of a workgroup all have queries
-    return nq >= (int64_t)SEARCH_WAVES * 32 * SEARCH_R * FIRST_G;
-}
-
-template <int CT, bool RAWT>
-static hipError_t launch_search_first_t(const FirstSearchArgs& a, int batch, hipStream_t s) {
+// Workgroups of the staged kernel that the current device holds at once (0: unknown).
+static int first_search_resident_wgs() {
     static DeviceCache resident_wgs;
     const long long resident = resident_wgs.get([](int dev) -> long long {
         int per_cu = 0;
         hipDeviceProp_t prop;
-        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, search_first_kernel<CT, FIRST_G, RAWT>, SEARCH_WAVES * 64, 0) != hipSuccess ||
+        if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, search_first_kernel<CT_F16, FIRST_G, true>, SEARCH_WAVES * 64, 0) != hipSuccess ||
             hipGetDeviceProperties(&prop, dev) != hipSuccess)
             return -1;
         return (long long)(per_cu > 0 ? per_cu : 1) * prop.multiProcessorCount;
     });
-    if (resident <= 0) return hipErrorUnknown;
-    int wgs = (int)resident / batch;
+    return resident > 0 ? (int)resident : 0;
+}
+static int first_search_wgs_per_pair(int batch) {
+    int wgs = first_search_resident_wgs() / batch;
     if (wgs >= 8) wgs &= ~7;
-    if (wgs < 1) wgs = 1;
+    return wgs < 1 ? 1 : wgs;
+}
+
+bool first_search_applies(int64_t nq, int64_t m, int batch) {
+    // at least one full quad of row groups, so that the four waves of a workgroup all have queries ...
+    if (nq < (int64_t)SEARCH_WAVES * 32 * SEARCH_R * FIRST_G || nq > 0x7FFFFFFF) return false;
+    // ... and chunks of at least FIRST_MIN_CHUNK tiles: one pair alone spreads over so many workgroups
+    // that a chunk would be a few turns long and mostly start-up (measured: a single 512x384 pair is
+    // 1.5 % slower with the staged kernel, two pairs are 2.5 % faster)
+    const int64_t row_groups = (nq + 32 * SEARCH_R * FIRST_G - 1) / (32 * SEARCH_R * FIRST_G);
+    const int64_t quads = (row_groups + SEARCH_WAVES - 1) / SEARCH_WAVES;
+    const int64_t chunks = first_search_wgs_per_pair(batch) / quads > 0 ? first_search_wgs_per_pair(batch) / quads : 1;
+    return (m + 31) / 32 / chunks >= FIRST_MIN_CHUNK;
+}
+
+template <int CT, bool RAWT>
+static hipError_t launch_search_first_t(const FirstSearchArgs& a, int batch, hipStream_t s) {
+    if (first_search_resident_wgs() <= 0) return hipErrorUnknown;
+    int wgs = first_search_wgs_per_pair(batch);
     const int row_groups = (a.s.nq + 32 * SEARCH_R * FIRST_G - 1) / (32 * SEARCH_R * FIRST_G);
     const int quads = (row_groups + SEARCH_WAVES - 1) / SEARCH_WAVES;
     const int64_t max_units = (int64_t)quads * ((a.s.m_tiles + FIRST_TURN - 1) / FIRST_TURN);

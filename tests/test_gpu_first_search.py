@@ -1,5 +1,6 @@
 """The first forward and the first backward search of fnn_reciprocal on 24-channel maps with a 16-bit
-compute format and at least 1536 seeds run in a kernel of their own: candidate tiles are staged through
+compute format, at least 1536 seeds and chunks of at least 32 candidate tiles per workgroup (many pairs, or
+large maps) run in a kernel of their own: candidate tiles are staged through
 LDS once per workgroup, and fp32 maps are read where the caller holds them (rounded on the way, the
 prepared copy written as a by-product, no prepare pass).  Exactly representable maps: everything must
 match the oracle bit for bit, whichever path a call takes, and the trace says which one it took."""
@@ -37,9 +38,9 @@ def exact(rng, rows, stride=24):
 
 @pytest.mark.parametrize("compute", ["f16", "bf16"])
 @pytest.mark.parametrize("n,m,n_seeds,batch,stride", [
-    (5000, 7013, 1600, 2, 24),     # partial tiles on both sides; 5 row groups: the second quad has three idle waves
-    (4096, 4128, 3072, 1, 28),     # rows 28 floats apart
-    (9001, 3333, 1536, 3, 24),     # exactly one quad
+    (5000, 7013, 1600, 64, 24),    # partial tiles on both sides; 5 row groups: the second quad has three idle waves
+    (4096, 4128, 3072, 64, 28),    # rows 28 floats apart
+    (9001, 9333, 1536, 64, 24),    # exactly one quad
 ])
 def test_fp32_maps_are_searched_where_they_are(compute, n, m, n_seeds, batch, stride):
     rng = np.random.default_rng(n + m)
@@ -54,39 +55,62 @@ def test_fp32_maps_are_searched_where_they_are(compute, n, m, n_seeds, batch, st
         check_reciprocal_exact(got, p, oracle.reciprocal(a[p][:, :24], b[p][:, :24], seeds[p], 10))
 
 
-def test_prepared_maps_take_the_staged_kernel_too_and_small_seed_sets_do_not():
+def test_prepared_maps_take_the_staged_kernel_too_and_small_calls_do_not():
     rng = np.random.default_rng(77)
-    n, m = 4096, 6400
-    a, b = exact(rng, n), exact(rng, m)
-    seeds = rng.integers(0, n, size=(1, 2000)).astype(np.int32)
-    ref = oracle.reciprocal(a, b, seeds[0], 10)
+    n, m, batch = 4096, 6400, 64
+    a = np.stack([exact(rng, n) for _ in range(batch)])
+    b = np.stack([exact(rng, m) for _ in range(batch)])
+    seeds = rng.integers(0, n, size=(batch, 2000)).astype(np.int32)
+    ref = [oracle.reciprocal(a[p], b[p], seeds[p], 10) for p in range(batch)]
+
+    def check(got):
+        for p in (0, 31, 63):
+            check_reciprocal_exact(got, p, ref[p])
+
     # stored in the compute format: read in place, no copy, staged first searches
     got, searches, _ = traced_reciprocal(dev(a).half(), dev(b).half(), dev(seeds), "f16")
     assert searches[:2] == [STAGED, STAGED]
-    check_reciprocal_exact(got, 0, ref)
+    check(got)
     # fp16 storage with padded rows: prepare pass, then the staged kernel on the prepared copy
-    wide_a = torch.zeros((n, 40), dtype=torch.float16, device="cuda:0")
-    wide_b = torch.zeros((m, 40), dtype=torch.float16, device="cuda:0")
-    wide_a[:, :24], wide_b[:, :24] = dev(a).half(), dev(b).half()
-    got, searches, _ = traced_reciprocal(wide_a[:, :24], wide_b[:, :24], dev(seeds), "f16")
+    wide_a = torch.zeros((batch, n, 40), dtype=torch.float16, device="cuda:0")
+    wide_b = torch.zeros((batch, m, 40), dtype=torch.float16, device="cuda:0")
+    wide_a[:, :, :24], wide_b[:, :, :24] = dev(a).half(), dev(b).half()
+    got, searches, _ = traced_reciprocal(wide_a[:, :, :24], wide_b[:, :, :24], dev(seeds), "f16")
     assert searches[:2] == [STAGED, STAGED]
-    check_reciprocal_exact(got, 0, ref)
+    check(got)
     # fewer seeds than one quad of row groups: the ordinary search kernel
-    few = seeds[:, :1535]
+    few = np.ascontiguousarray(seeds[:, :1535])
     got, searches, _ = traced_reciprocal(dev(a), dev(b), dev(few), "f16")
     assert STAGED not in searches
-    check_reciprocal_exact(got, 0, oracle.reciprocal(a, b, few[0], 10))
+    check_reciprocal_exact(got, 5, oracle.reciprocal(a[5], b[5], few[5], 10))
+    # one pair alone: so many workgroups per pair that a chunk would be a few tiles: the ordinary kernels
+    got, searches, _ = traced_reciprocal(dev(a[7]), dev(b[7]), dev(seeds[7:8]), "f16")
+    assert STAGED not in searches
+    check_reciprocal_exact(got, 0, ref[7])
     # fp32 products: the ordinary kernels
     got, searches, _ = traced_reciprocal(dev(a), dev(b), dev(seeds), "f32")
     assert STAGED not in searches
-    check_reciprocal_exact(got, 0, ref)
+    check(got)
 
 
 def test_misaligned_fp32_rows_fall_back_to_the_prepare_pass():
     rng = np.random.default_rng(78)
-    n, m = 4096, 4096
-    a, b = exact(rng, n, 25), exact(rng, m, 25)     # rows 25 floats apart: no 16-byte alignment
-    seeds = rng.integers(0, n, size=(1, 1600)).astype(np.int32)
-    got, searches, _ = traced_reciprocal(dev(a)[:, :24], dev(b)[:, :24], dev(seeds), "f16")
+    n, m, batch = 4096, 4096, 64
+    a = np.stack([exact(rng, n, 25) for _ in range(batch)])     # rows 25 floats apart: no 16-byte alignment
+    b = np.stack([exact(rng, m, 25) for _ in range(batch)])
+    seeds = rng.integers(0, n, size=(batch, 1600)).astype(np.int32)
+    got, searches, prep_ms = traced_reciprocal(dev(a)[:, :, :24], dev(b)[:, :, :24], dev(seeds), "f16")
     assert searches[:2] == [STAGED, STAGED]           # the staged kernel, on the copy the prepare pass made
-    check_reciprocal_exact(got, 0, oracle.reciprocal(a[:, :24], b[:, :24], seeds[0], 10))
+    for p in (0, 63):
+        check_reciprocal_exact(got, p, oracle.reciprocal(a[p][:, :24], b[p][:, :24], seeds[p], 10))
+
+
+def test_single_large_pair_is_staged():
+    """One pair is staged when its maps are large enough for long chunks (1024x768: 24576 tiles)."""
+    rng = np.random.default_rng(79)
+    n = 1024 * 768
+    a, b = exact(rng, n), exact(rng, n)
+    seeds = rng.integers(0, n, size=(1, 1536)).astype(np.int32)
+    got, searches, _ = traced_reciprocal(dev(a), dev(b), dev(seeds), "bf16")
+    assert searches[:2] == [STAGED, STAGED]
+    check_reciprocal_exact(got, 0, oracle.reciprocal(a, b, seeds[0], 10))
