@@ -41,13 +41,17 @@
  *    kernels and never synchronises) once the same entry point has run eagerly on the device,
  *    which fills that cache.
  *  - The maps are read by the enqueued work and never written: keep them alive and unchanged
- *    until the stream has passed the call.  fnn_nearest and fnn_reciprocal copy a map into the
- *    workspace (cast to the compute format, rows padded) unless the caller's array already
- *    is what that copy would be -- stored in the compute format, d in {16, 24, 32} (16-bit
- *    formats) or a multiple of 8 (FNN_F32), row_stride == d, n a multiple of 32, 16-byte
- *    aligned, the batch's maps equally spaced in memory, no flags -- in which case it is
- *    searched where it is and that side costs no copy.  Results do not depend on which way
- *    a map took.
+ *    until the stream has passed the call.  The searches work on a prepared copy of each map in
+ *    the workspace (cast to the compute format, rows padded to whole 32-pixel tiles).  Two cases
+ *    need no separate copy pass, and results do not depend on which way a map took:
+ *    (a) the caller's array already is what the copy would be -- stored in the compute format,
+ *    d in {16, 24, 32} (16-bit formats) or a multiple of 8 (FNN_F32), row_stride == d, n a
+ *    multiple of 32, 16-byte aligned, the batch's maps equally spaced in memory, no flags --
+ *    then fnn_nearest and fnn_reciprocal search it where it is;
+ *    (b) fnn_reciprocal on fp32 maps with d == 24, a 16-bit compute format, no flags, rows
+ *    that start on 16-byte boundaries (row_stride a multiple of 4), at least 1536 seeds and
+ *    enough work per pair: the first forward and the first backward search read the caller's
+ *    rows, round them on the way and leave the prepared copy behind for the later searches.
  *  - Errors are return codes only.  Argument errors are detected on the host before
  *    anything is enqueued (outputs untouched).  Index arrays live in device memory and are
  *    NOT range-checked: a seed or query index outside [0, n) is undefined behaviour.

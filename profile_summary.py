@@ -142,21 +142,33 @@ def hbm_traffic() -> None:
     result = {"source": f"profiles/hbm_traffic_{SUFFIX}.md (rocprofv3 FETCH_SIZE + WRITE_SIZE, scaled by a 256 MiB copy)"}
     if s_rd is not None and bench:
         # bench.py runs its batched reciprocal steps first: one call that builds the outputs, the
-        # warm-up, the timed steps and the traced steps, 2 * max_iter search launches each
+        # warm-up, the timed steps and the traced steps, 2 * max_iter search launches each.  The first
+        # two of a step are launches of search_first_kernel (the staged kernel that also reads the
+        # caller's fp32 maps and writes the prepared copies), the rest of search_kernel.
         per_step = int(round(bench["roofline"]["launches_per_step"]))
-        n_batched = (1 + bench["warmup"] + 2 * bench["steps"]) * per_step
-        s_writes = [v for k, v in per["write"].items() if k.startswith("search_kernel")][0]
-        rd_mib = [x * cal["fetch"] / 1024 for x in s_list[:n_batched]]
-        wr_mib = [x * cal["write"] / 1024 for x in s_writes[:n_batched]]
-        result["search_kernel_bytes_per_launch"] = round((sum(rd_mib) + sum(wr_mib)) / n_batched * 1048576)
-        live = [x for x in rd_mib if x > 1.0]
+        n_steps = 1 + bench["warmup"] + 2 * bench["steps"]
+        def mib(run, prefix, count):
+            rows = [v for k, v in per[run].items() if k.startswith(prefix)]
+            return [x * cal[run] / 1024 for x in rows[0][:count]] if rows else []
+        first_rd, first_wr = mib("fetch", "search_first_kernel", 2 * n_steps), mib("write", "search_first_kernel", 2 * n_steps)
+        n_first = len(first_rd)
+        n_rest = n_steps * per_step - n_first
+        rest_rd, rest_wr = mib("fetch", "search_kernel", n_rest), mib("write", "search_kernel", n_rest)
+        total = sum(first_rd) + sum(first_wr) + sum(rest_rd) + sum(rest_wr)
+        result["search_kernel_bytes_per_launch"] = round(total / (n_steps * per_step) * 1048576)
+        live = [x for x in rest_rd if x > 1.0]
         alg = bench["roofline_hbm"]["bytes_per_launch"]
-        lines += ["", "## search_kernel (the launches of the 16-pair reciprocal steps)", "",
-                  f"Read MiB per launch, the {per_step} launches of the last step, in launch order: " + ", ".join(f"{x:.1f}" for x in rd_mib[-per_step:]), "",
-                  f"Average HBM bytes per launch over these {n_batched} launches (read + written): {result['search_kernel_bytes_per_launch']/1e6:.1f} MB; "
-                  f"algorithmic bytes per launch (bench.py `roofline_hbm.bytes_per_launch`): {alg/1e6:.1f} MB.  A live search of 16 pairs must read "
-                  f"16 x 196608 x 48 B = 151 MB = 144 MiB once; the live launches read {sum(live)/max(len(live),1):.1f} MiB on average (the last-level "
-                  "cache keeps part of a map between the searches of a step), the launches after the last seed has converged read nothing.", ""]
+        lines += ["", "## the search launches of the 16-pair reciprocal steps", "",
+                  f"search_first_kernel (first forward and first backward search of a step; fp32 maps in, prepared fp16 copy out), last two launches: "
+                  + ", ".join(f"{r:.1f} MiB read / {w:.1f} MiB written" for r, w in zip(first_rd[-2:], first_wr[-2:]))
+                  + ".  The fp32 maps of 16 pairs are 288 MiB, their fp16 copy 144 MiB.", "",
+                  f"search_kernel, read MiB per launch, the {per_step - 2} launches of the last step, in launch order: "
+                  + ", ".join(f"{x:.1f}" for x in rest_rd[-(per_step - 2):]), "",
+                  f"Average HBM bytes per search launch over these {n_steps * per_step} launches (read + written): "
+                  f"{result['search_kernel_bytes_per_launch']/1e6:.1f} MB; algorithmic bytes per launch (bench.py `roofline_hbm.bytes_per_launch`): "
+                  f"{alg/1e6:.1f} MB.  A live search of 16 prepared maps must read 16 x 196608 x 48 B = 151 MB = 144 MiB once; the live launches of "
+                  f"search_kernel read {sum(live)/max(len(live),1):.1f} MiB on average (the last-level cache keeps part of a map between the searches "
+                  "of a step), the launches after the last seed has converged read nothing.", ""]
     if d_rd is not None:
         d_us = times.get([k for k in times if k.startswith("dense_kernel")][0]) if any(k.startswith("dense_kernel") for k in times) else None
         rate = ""
@@ -186,7 +198,11 @@ def mfma_utilisation() -> None:
     for r in rows:
         disp[(r["Dispatch_Id"], r["Kernel_Name"])][r["Counter_Name"]] = float(r["Counter_Value"])
     trace = {r["Dispatch_Id"]: (int(r["End_Timestamp"]) - int(r["Start_Timestamp"])) for r in trace_rows}
-    searches = sorted([(k, v) for k, v in disp.items() if "search_kernel" in k[1]], key=lambda kv: -kv[1].get("SQ_INSTS_MFMA", 0))
+    searches = sorted([(k, v) for k, v in disp.items() if "search_first_kernel" in k[1]], key=lambda kv: -kv[1].get("SQ_INSTS_MFMA", 0))
+    first_name = "search_first_kernel"
+    if not searches:
+        searches = sorted([(k, v) for k, v in disp.items() if "search_kernel" in k[1]], key=lambda kv: -kv[1].get("SQ_INSTS_MFMA", 0))
+        first_name = "search_kernel"
     denses = [(k, v) for k, v in disp.items() if "dense_kernel<" in k[1]]
     if not searches or not denses:
         return
@@ -211,7 +227,7 @@ def mfma_utilisation() -> None:
              "    " + COMMANDS["mfma"], "",
              "Per dispatch.  GRBM_GUI_ACTIVE is summed over the 8 XCDs, SQ_VALU_MFMA_BUSY_CYCLES over the 1024 SIMDs; SQ_INSTS_* count wave instructions",
              "(SQ_INSTS_VALU includes the matrix instructions).  A 32x32 product = one K=16 plus one K=8 matrix instruction.", "",
-             "| quantity | search_kernel, first search of a step (16 x 3072 queries) | dense_kernel (cfg 3) |", "|---|---|---|"]
+             f"| quantity | {first_name}, first search of a step (16 x 3072 queries) | dense_kernel (cfg 3) |", "|---|---|---|"]
     lines += [f"| {n} | {x} | {y} |" for n, x, y in zip(names, a, b)]
     lines += ["", "Of the vector instructions per product, 8 (search) and 16 (dense) are the three-input maxima that fold the scores; the rest is location",
               "tracking, address arithmetic, register copies and (dense) the per-super-block column flush."]
@@ -236,8 +252,10 @@ def lds_l2() -> None:
             if k.startswith(prefix) and counter in v:
                 return max(v[counter]) if how == "max" else sum(v[counter]) / len(v[counter])
         return float("nan")
-    kernels = [("search_kernel", "max", "search_kernel, first search of a step (largest launch)"), ("resolve_kernel", "max", "resolve_kernel, first resolve of a step"),
-               ("dense_kernel<", "mean", "dense_kernel (cfg 3)"), ("prep_f32_kernel", "max", "prepare pass (cfg 4, both maps of 16 pairs)")]
+    kernels = [("search_first_kernel", "max", "search_first_kernel, first search of a step (fp32 maps in, LDS-staged)"),
+               ("search_kernel", "max", "search_kernel, largest launch (third search of a step: 16 x ~1450 queries)"),
+               ("resolve_kernel", "max", "resolve_kernel, first resolve of a step"),
+               ("dense_kernel<", "mean", "dense_kernel (cfg 3)"), ("prep_f32_kernel", "max", "prepare pass, largest launch (the dense legs: both maps of a pair)")]
     lines = ["# LDS and cache counters (rocprofv3 SQ / TCP / TCC counters): bench.py workloads", "", "Commands (two counter runs):", "",
              "    " + COMMANDS["lds"], "    " + COMMANDS["l2"], "",
              "Per dispatch; SQ_BUSY_CYCLES is summed over the shader engines, the cache counters over all channels.", "",
