@@ -80,6 +80,8 @@ def main() -> int:
                     help="also time the same batch with the squared-distance dist_func (FNN_FLAG_L2)")
     ap.add_argument("--split", action="store_true",
                     help="also time the batch with FNN_FLAG_SPLIT (fp32-grade scores from three fp16 products) and with fp32 products")
+    ap.add_argument("--batch-sweep", action="store_true",
+                    help="also time the same workload at 1, 2, 4, 8, 32 and 64 pairs per call")
     ap.add_argument("--no-ceiling", action="store_true",
                     help="skip the measurement of what the device sustains on the kernels' bare instruction mix (about a second)")
     ap.add_argument("--f16-maps", action="store_true",
@@ -268,6 +270,8 @@ def main() -> int:
     # ---- optional: the same batch as raw head outputs (normalisation fused into the prepare pass) --
     if args.normalize:
         nout = fnn.fnn_reciprocal(d1, d2, seeds, MAX_ITER, compute, normalize=True, workspace=ws)
+        for _ in range(args.warmup):
+            fnn.fnn_reciprocal(d1, d2, seeds, MAX_ITER, compute, out=nout, normalize=True, workspace=ws)
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         for _ in range(args.steps):
@@ -289,6 +293,8 @@ def main() -> int:
         tdt = torch.float16 if compute == "f16" else torch.bfloat16
         h1, h2 = d1.to(tdt), d2.to(tdt)
         hout = fnn.fnn_reciprocal(h1, h2, seeds, MAX_ITER, compute, workspace=ws)
+        for _ in range(args.warmup):
+            fnn.fnn_reciprocal(h1, h2, seeds, MAX_ITER, compute, out=hout, workspace=ws)
         torch.cuda.synchronize()
         same = all(torch.equal(hout[k], out[k]) for k in ("pairs", "n_pairs", "seed_i", "seed_j", "seed_iter"))
         t0 = time.perf_counter()
@@ -307,6 +313,8 @@ def main() -> int:
         need = fnn.fnn_workspace_bytes_opts(BATCH, N_PIX, N_PIX, D, n_seeds, compute, l2=True)
         lws = torch.empty(need, dtype=torch.uint8, device=dev)
         lout = fnn.fnn_reciprocal(d1, d2, seeds, MAX_ITER, compute, l2=True, workspace=lws)
+        for _ in range(args.warmup):
+            fnn.fnn_reciprocal(d1, d2, seeds, MAX_ITER, compute, out=lout, l2=True, workspace=lws)
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         for _ in range(args.steps):
@@ -320,6 +328,27 @@ def main() -> int:
         }
         del lws
 
+    # ---- optional: the same workload at other batch sizes ---------------------------------------------
+    if args.batch_sweep:
+        sweep = {}
+        for nb in (1, 2, 4, 8, 32, 64):
+            pick = [p % BATCH for p in range(nb)]
+            b1, b2, bseeds = d1[pick].contiguous(), d2[pick].contiguous(), seeds[pick].contiguous()
+            bws = torch.empty(fnn.fnn_workspace_bytes(nb, N_PIX, N_PIX, D, n_seeds, compute), dtype=torch.uint8, device=dev)
+            bout = fnn.fnn_reciprocal(b1, b2, bseeds, MAX_ITER, compute, workspace=bws)
+            for _ in range(3):
+                fnn.fnn_reciprocal(b1, b2, bseeds, MAX_ITER, compute, out=bout, workspace=bws)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(args.steps):
+                fnn.fnn_reciprocal(b1, b2, bseeds, MAX_ITER, compute, out=bout, workspace=bws)
+            torch.cuda.synchronize()
+            b_s = (time.perf_counter() - t0) / args.steps
+            sweep[str(nb)] = {"ms_per_call": round(b_s * 1e3, 4), "pairs_per_s": round(nb / b_s, 1)}
+            del b1, b2, bseeds, bws, bout
+        sweep[str(BATCH)] = {"ms_per_call": round(ms_per_step, 4), "pairs_per_s": round(pairs_per_s, 1)}
+        result["batch_sweep"] = sweep
+
     # ---- optional: the same batch at fp32-grade precision, two ways ---------------------------------
     if args.split:
         variants = {}
@@ -327,6 +356,7 @@ def main() -> int:
             need = fnn.fnn_workspace_bytes_opts(BATCH, N_PIX, N_PIX, D, n_seeds, comp, **kw)
             sws = torch.empty(need, dtype=torch.uint8, device=dev)
             sout = fnn.fnn_reciprocal(d1, d2, seeds, MAX_ITER, comp, workspace=sws, **kw)
+            fnn.fnn_reciprocal(d1, d2, seeds, MAX_ITER, comp, out=sout, workspace=sws, **kw)
             torch.cuda.synchronize()
             reps = max(args.steps // 4, 3)
             t0 = time.perf_counter()
