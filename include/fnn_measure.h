@@ -19,8 +19,10 @@ extern "C" {
  * report each kernel's device-side duration.  fnn_trace_end waits for the traced kernels,
  * writes min(*n_recorded, capacity) entries (kinds[i] names the kernel, see
  * fnn_trace_kind_name; milliseconds[i] is its duration, in launch order; details[i], if the
- * array is not NULL, is the launch shape the host chose: for the search kernel the number of
- * groups of four 32-query blocks a wave keeps resident, 0 for the other kernels) to HOST
+ * array is not NULL, is the launch shape the host chose: for a search the number of groups of
+ * four 32-query blocks a wave keeps resident, plus 100 when the kernel that stages the candidate
+ * tiles through LDS ran; for the dense pass-1 kernel 1 when the variant that stages the query
+ * blocks through LDS ran; 0 otherwise) to HOST
  * arrays and closes the trace.  The trace is process-wide state and not thread-safe, and must
  * not be open during HIP graph capture.
  */

@@ -120,6 +120,37 @@ __device__ __forceinline__ void locate_first_lanes(const float (&x)[16], const f
     }
 }
 
+// Best query of each resident candidate inside one super-block: a transposing reduction
+// leaves the maximum of register v with the lanes that hold v; the 16 maxima of a half go
+// round through the wave's LDS words so that every lane can test its own value against them;
+// the lowest lane that attains each maximum is read off the comparison mask and handed to the
+// holding lane, which files the key (one LDS operation per tile).
+__device__ __forceinline__ void dense_flush_columns(const float (&cmax)[DENSE_J][16], float* lds_tops, u64* lds_col_keys,
+                                                    int sbg, int lane, int h, int held) {
+    const float ninf = -__builtin_inff();
+#pragma unroll
+    for (int jt = 0; jt < DENSE_J; ++jt) {
+        const float top = transpose_max16(cmax[jt], lane);
+        lds_tops[h * 16 + held] = top;  // the two rows of a half store the same value
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        float tops[16];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const float4 t4 = reinterpret_cast<const float4*>(lds_tops + h * 16)[q];
+            tops[4 * q + 0] = t4.x;
+            tops[4 * q + 1] = t4.y;
+            tops[4 * q + 2] = t4.z;
+            tops[4 * q + 3] = t4.w;
+        }
+        __builtin_amdgcn_wave_barrier();
+        int first_lane = 0;
+        locate_first_lanes<0>(cmax[jt], tops, first_lane);
+        if ((lane & 16) == 0 && top != ninf)
+            atomicMax(&lds_col_keys[jt * 32 + tile_row(held, h)], pack_key(top, sbg * 32 + first_lane));
+    }
+}
+
 // The 16-bit rows of the two-term representation (96 to 192 bytes) need more than half the
 // register file for the resident tiles, the query ring and the result buffers: one wave per
 // SIMD there.  Everything else runs two (measured: fp16 d = 24 2.4 ms against 3.6 ms with one
@@ -128,18 +159,16 @@ template <int CT, int DP>
 constexpr int dense_waves_per_simd() {
     return (CT != CT_F32 && Ops<CT, DP>::ROW_BYTES > 64) ? 1 : 2;
 }
+// The work of one workgroup of pass 1: its super-blocks of queries swept past its candidate groups.
 template <int CT, int DP>
-__global__ __launch_bounds__(DENSE_WAVES * 64) __attribute__((amdgpu_waves_per_eu(dense_waves_per_simd<CT, DP>())))
-void dense_kernel(DenseArgs a) {
+// lds_row_keys: [sb_per_wg * S * 32] keys indexed by the query's stored slot in the workgroup's
+// range; lds_col_keys: J * 32 keys and lds_tops: 32 floats of the calling wave.
+__device__ __forceinline__ void dense_workgroup(const DenseArgs& a, u64* lds_row_keys, u64* lds_col_keys, float* lds_tops) {
     using O = Ops<CT, DP>;
     using Frag = typename O::Frag;
     constexpr int J = DENSE_J, S = DENSE_S;
-    extern __shared__ u64 lds[];
-    u64* lds_row_keys = lds;  // [sb_per_wg * S * 32], indexed by the query's stored slot in the workgroup's range
     const int lane = threadIdx.x & 63, c = lane & 31, h = lane >> 5;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    u64* lds_col_keys = lds + (size_t)a.sb_per_wg * S * 32 + wave * (J * 32);  // this wave's J*32 candidates
-    float* lds_tops = reinterpret_cast<float*>(lds + (size_t)a.sb_per_wg * S * 32 + DENSE_WAVES * (J * 32)) + wave * 32;
     const int held = held_register(lane);
     const int b = blockIdx.z;
     const float ninf = -__builtin_inff();
@@ -183,36 +212,274 @@ void dense_kernel(DenseArgs a) {
             else
                 dense_sweep<CT, DP, false>(a, cand, cmax, qbase, sbg, tbase, lds_row_keys + sb * S * 32, tbase / J, c, h);
 
-            // best query of each resident candidate inside this super-block: a transposing
-            // reduction leaves the maximum of register v with the lanes that hold v; the 16
-            // maxima of a half go round through the wave's LDS words so that every lane can
-            // test its own value against them; the lowest lane that attains each maximum is
-            // read off the comparison mask and handed to the holding lane, which files the key
-            // (one LDS operation per tile)
-#pragma unroll
-            for (int jt = 0; jt < J; ++jt) {
-                const float top = transpose_max16(cmax[jt], lane);
-                lds_tops[h * 16 + held] = top;  // the two rows of a half store the same value
-                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-                __builtin_amdgcn_wave_barrier();
-                float tops[16];
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const float4 t4 = reinterpret_cast<const float4*>(lds_tops + h * 16)[q];
-                    tops[4 * q + 0] = t4.x;
-                    tops[4 * q + 1] = t4.y;
-                    tops[4 * q + 2] = t4.z;
-                    tops[4 * q + 3] = t4.w;
-                }
-                __builtin_amdgcn_wave_barrier();
-                int first_lane = 0;
-                locate_first_lanes<0>(cmax[jt], tops, first_lane);
-                if ((lane & 16) == 0 && top != ninf)
-                    atomicMax(&lds_col_keys[jt * 32 + tile_row(held, h)], pack_key(top, sbg * 32 + first_lane));
-            }
+            dense_flush_columns(cmax, lds_tops, lds_col_keys, sbg, lane, h, held);
         }
 
         // this wave's candidates are complete for the workgroup's query range
+#pragma unroll
+        for (int jt = 0; jt < J; ++jt) {
+            const int j = (tbase + jt) * 32 + c;
+            const u64 key = lds_col_keys[jt * 32 + c];
+            if (h == 0 && j < a.m && key) atomicMax(&col_keys[j], key);
+        }
+    }
+
+    __syncthreads();
+    for (int slot = threadIdx.x; slot < n_sb * S * 32; slot += blockDim.x) {
+        const u64 key = lds_row_keys[slot];
+        const int i = segment_pixel(sb0 + slot / (S * 32), (slot / 32) % S, slot % 32);
+        if (key && i < a.n) atomicMax(&row_keys[i], key);
+    }
+}
+
+template <int CT, int DP>
+__global__ __launch_bounds__(DENSE_WAVES * 64) __attribute__((amdgpu_waves_per_eu(dense_waves_per_simd<CT, DP>())))
+void dense_kernel(DenseArgs a) {
+    extern __shared__ u64 lds[];
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    u64* col_keys = lds + (size_t)a.sb_per_wg * DENSE_S * 32;
+    dense_workgroup<CT, DP>(a, lds, col_keys + wave * (DENSE_J * 32),
+                            reinterpret_cast<float*>(col_keys + DENSE_WAVES * (DENSE_J * 32)) + wave * 32);
+}
+
+// ---- pass 1 with the query blocks staged through LDS (16-bit formats, 24 channels) ----------
+// The four waves of a workgroup sweep the SAME query blocks past their own resident tiles, so
+// in dense_kernel every block crosses the vector memory path four times per workgroup.  Here a
+// workgroup fetches each block once: a turn is DENSE_TURN_BLOCKS query blocks (four steps);
+// while the waves compute on one LDS slot, the next turn's blocks -- two per wave -- are on
+// their way into the other slot through direct global->LDS loads, which occupy no registers.
+// One workgroup barrier per turn, taken at the start of the turn's last step: by then every wave
+// holds that step's blocks in registers, so the slot can be refilled at once for the turn after
+// next, and the first blocks of the next turn can be read from the other slot in time for the
+// software pipeline to run on across the turn boundary.  Arithmetic, keys and results are those
+// of dense_kernel.
+#ifndef FNN_DENSE_STAGED
+#define FNN_DENSE_STAGED 1
+#endif
+constexpr bool DENSE_STAGED = FNN_DENSE_STAGED != 0;
+constexpr int DENSE_TURN_STEPS = 4;
+constexpr int DENSE_TURN_BLOCKS = 2 * DENSE_TURN_STEPS;
+constexpr int DENSE_TURNS = DENSE_S / DENSE_TURN_BLOCKS;  // turns per super-block
+static_assert(DENSE_S % DENSE_TURN_BLOCKS == 0 && DENSE_TURNS % 2 == 0, "a sweep is a whole, even number of turns");
+static_assert(DENSE_TURN_BLOCKS == 2 * DENSE_WAVES, "every wave stages two blocks of a turn");
+static_assert(DENSE_TURN_STEPS % 2 == 0, "the steps of a turn alternate two register sets");
+
+// One slot of the stage.  The two slots are separate LDS variables, so that the compiler can tell
+// a read of one slot from a load in flight into the other and need not wait for it.
+struct DenseSlot {
+    uint4 lo[DENSE_TURN_BLOCKS][64];  // channels 8h..8h+7 of lane (c, h)'s row
+    uint2 hi[DENSE_TURN_BLOCKS][64];  // channels 16+4h..16+4h+3
+};
+
+#define FNN_LDS_PTR(p) ((void __attribute__((address_space(3)))*)(p))
+
+// This wave's two blocks of the turn that starts at `turn` (uniform; 48-byte rows) into `slot`.
+// A direct load writes lane l's bytes at the LDS base + l * size: 16 bytes per lane give the
+// `lo` words in lane order; the `hi` words (8 bytes per reading lane) take two 4-byte loads in
+// which lane l fetches word l & 1 of reading lane l >> 1 (first half) or 32 + (l >> 1).
+__device__ __forceinline__ void dense_stage_turn(DenseSlot& st, const char* turn, int wave, int lane) {
+    // The lane number is read afresh and the byte offsets are recomputed from it (a few
+    // operations per turn): held across the sweep they were spilled, and a reload behind the
+    // loads issued here would wait for all of them.
+    (void)lane;
+    uint32_t l;
+    asm volatile("v_mbcnt_lo_u32_b32 %0, -1, 0\n\tv_mbcnt_hi_u32_b32 %0, -1, %0" : "=v"(l));
+    const uint32_t c = l & 31, h = l >> 5, pair = l >> 1, word = l & 1;
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const int blk = 2 * wave + i;
+        const char* src = turn + (int64_t)blk * (32 * 48);
+        __builtin_amdgcn_global_load_lds((const void*)(src + (c * 48u + 16u * h)), FNN_LDS_PTR(&st.lo[blk][0]), 16, 0, 0);
+        __builtin_amdgcn_global_load_lds((const void*)(src + (pair * 48u + 32u + 4u * word)), FNN_LDS_PTR(&st.hi[blk][0]), 4, 0, 0);
+        __builtin_amdgcn_global_load_lds((const void*)(src + (pair * 48u + 40u + 4u * word)), FNN_LDS_PTR(&st.hi[blk][32]), 4, 0, 0);
+    }
+}
+
+// Where the workgroup's query stream stands: turn k of the stream is turn k % DENSE_TURNS of
+// super-block (k / DENSE_TURNS) % n_sb (the stream repeats for every candidate group).
+struct DenseStream {
+    const char* d1;   // first super-block of the workgroup
+    int n_sb;
+    int total;        // turns in the whole stream
+    __device__ __forceinline__ const char* turn(int k) const {
+        k = min(k, total - 1);  // past the end: re-read the last turn, never used
+        const int sb = (k / DENSE_TURNS) % n_sb, t = k % DENSE_TURNS;
+        return d1 + ((int64_t)sb * DENSE_S + (int64_t)t * DENSE_TURN_BLOCKS) * (32 * 48);
+    }
+};
+
+// One super-block swept past the wave's resident tiles, blocks taken from the LDS stage.  k0 is
+// the stream turn the sweep starts with (even: slot 0); on entry that turn is staged and
+// visible, and turn k0 + 1 is on its way.  The same holds for k0 + DENSE_TURNS on return.
+template <int CT>
+__device__ __forceinline__ void dense_sweep_staged(const DenseArgs& a, const typename Ops<CT, 24>::Frag (&cand)[DENSE_J],
+                                                   float (&cmax)[DENSE_J][16], DenseSlot& slot0, DenseSlot& slot1, const DenseStream& stream,
+                                                   int k0, u64* lds_rows, int unit_row, int wave, int lane) {
+    using O = Ops<CT, 24>;
+    using Frag = typename O::Frag;
+    constexpr int J = DENSE_J;
+    const int c = lane & 31, h = lane >> 5;
+    const float ninf = -__builtin_inff();
+    // Lane l's fragment of a staged block: 16 bytes at l * 16 and 8 bytes at l * 8.  The lane offset
+    // is produced afresh where it is needed (three operations per step): kept in a register across
+    // the unrolled sweep it was spilled, and a reload behind the direct loads waits for all of them.
+    auto lane_offset = [&]() {
+        uint32_t o;
+        asm volatile("v_mbcnt_lo_u32_b32 %0, -1, 0\n\tv_mbcnt_hi_u32_b32 %0, -1, %0\n\tv_lshlrev_b32 %0, 4, %0" : "=v"(o));
+        return o;
+    };
+    auto staged = [&](const DenseSlot& st, int blk, uint32_t o16) {
+        Frag f;
+        f.lo = *reinterpret_cast<const uint4*>(reinterpret_cast<const char*>(&st.lo[blk][0]) + o16);
+        f.hi = *reinterpret_cast<const uint2*>(reinterpret_cast<const char*>(&st.hi[blk][0]) + (o16 >> 1));
+        return f;
+    };
+    // Best candidate of the step's two queries over this wave's J tiles -> workgroup table (lane half
+    // 0 files block t, half 1 block t + 1).  The updates of a turn are filed together just before
+    // the turn's barrier, where the loads in flight have to be waited for anyway: the compiler
+    // orders every LDS atomic after them.
+    float row_best[DENSE_TURN_STEPS];
+    auto file_row_best = [&](int s, int t) { atomicMax(&lds_rows[(t + h) * 32 + c], pack_key(row_best[s], unit_row)); };
+    Frag q[2][2];  // [register set][block of the step]
+    {
+        const uint32_t o16 = lane_offset();
+        q[0][0] = staged(slot0, 0, o16);
+        q[0][1] = staged(slot0, 1, o16);
+    }
+    f32x16 pa[2], pb[2];
+    pa[0] = O::mma(cand[0], q[0][0]);
+    pb[0] = O::mma(cand[0], q[0][1]);
+
+    auto turn = [&](int tt, auto slot_tag) {
+        constexpr int SLOT = decltype(slot_tag)::value;
+        DenseSlot& mine = SLOT ? slot1 : slot0;
+        DenseSlot& next = SLOT ? slot0 : slot1;
+#pragma unroll
+        for (int s = 0; s < DENSE_TURN_STEPS; ++s) {
+            const int set = s & 1, other = set ^ 1;
+            const int t = tt * DENSE_TURN_BLOCKS + 2 * s;  // first query block of the step
+            const uint32_t o16 = lane_offset();
+            if (s + 1 < DENSE_TURN_STEPS) {
+                q[other][0] = staged(mine, 2 * s + 2, o16);
+                q[other][1] = staged(mine, 2 * s + 3, o16);
+            } else {
+                // every wave holds this step's blocks: the next turn has landed (the barrier
+                // waits for this wave's loads first), and this slot is free for the one after
+                {   // the last step of the turn before (in the sweep's first turn: step 0 once more, which is
+                    // harmless and keeps this stretch free of branches)
+                    const float carried = tt > 0 ? row_best[DENSE_TURN_STEPS - 1] : row_best[0];
+                    const int carried_t = tt > 0 ? t - DENSE_TURN_BLOCKS : 0;
+                    atomicMax(&lds_rows[(carried_t + h) * 32 + c], pack_key(carried, unit_row));
+                }
+#pragma unroll
+                for (int done = 0; done + 1 < DENSE_TURN_STEPS; ++done) file_row_best(done, tt * DENSE_TURN_BLOCKS + 2 * done);
+                __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this wave's share of the next turn is in LDS
+                __syncthreads();
+                dense_stage_turn(mine, stream.turn(k0 + tt + 2), wave, lane);
+                q[other][0] = staged(next, 0, o16);
+                q[other][1] = staged(next, 1, o16);
+            }
+            float ra = ninf, rb = ninf;
+#pragma unroll
+            for (int jt = 0; jt < J; ++jt) {
+                const int cur = jt & 1, nxt = cur ^ 1;
+                if (jt + 1 < J) {
+                    pa[nxt] = O::mma(cand[jt + 1], q[set][0]);
+                    pb[nxt] = O::mma(cand[jt + 1], q[set][1]);
+                } else {  // tile 0 against the next step's blocks (after the last step: computed, never folded)
+                    pa[nxt] = O::mma(cand[0], q[other][0]);
+                    pb[nxt] = O::mma(cand[0], q[other][1]);
+                }
+                ra = fold16f(ra, pa[cur]);
+                rb = fold16f(rb, pb[cur]);
+#pragma unroll
+                for (int v = 0; v < 16; ++v) cmax[jt][v] = max3f(cmax[jt][v], pa[cur][v], pb[cur][v]);
+            }
+            row_best[s] = cross_half_max(ra, rb);
+            __builtin_amdgcn_sched_barrier(0);  // steps are scheduled one by one, as in the rolled loop of dense_kernel
+        }
+    };
+    for (int tt = 0; tt < DENSE_TURNS; tt += 2) {
+        turn(tt, std::integral_constant<int, 0>{});
+        turn(tt + 1, std::integral_constant<int, 1>{});
+    }
+    file_row_best(DENSE_TURN_STEPS - 1, DENSE_S - 2);
+}
+
+template <int CT>
+__global__ __launch_bounds__(DENSE_WAVES * 64) __attribute__((amdgpu_waves_per_eu(2)))
+void dense_staged_kernel(DenseArgs a) {
+    using O = Ops<CT, 24>;
+    using Frag = typename O::Frag;
+    constexpr int J = DENSE_J, S = DENSE_S;
+    // Every LDS object is a variable of its own (no dynamic LDS): the compiler then knows that the
+    // key tables are not the stage, and does not wait for a load in flight when it updates them.
+    __shared__ DenseSlot slot0, slot1;
+    __shared__ u64 row_key_table[S * 32];               // one super-block per workgroup
+    __shared__ u64 col_key_table[DENSE_WAVES][J * 32];
+    __shared__ float top_table[DENSE_WAVES][32];
+    u64* lds_row_keys = row_key_table;
+    const int lane = threadIdx.x & 63, c = lane & 31, h = lane >> 5;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    u64* lds_col_keys = col_key_table[wave];
+    float* lds_tops = top_table[wave];
+    const int held = held_register(lane);
+    const int b = blockIdx.z;
+    const float ninf = -__builtin_inff();
+
+    const int sb0 = blockIdx.y;  // launched with one super-block per workgroup
+    const int n_sb = 1;
+    const int group0 = blockIdx.x * a.groups_per_wg;
+    // groups of this workgroup that hold a candidate tile at all (uniform)
+    const int groups_left = (a.m_tiles - group0 * DENSE_TILES_PER_GROUP + DENSE_TILES_PER_GROUP - 1) / DENSE_TILES_PER_GROUP;
+    const int n_groups = min(a.groups_per_wg, groups_left);
+    if (n_groups <= 0 || n_sb <= 0) return;
+    // A workgroup that meets padding -- queries past n or candidates past m -- takes the
+    // unstaged path, whose sweep can mask them: at most one row and one column of workgroups.
+    if ((int64_t)(sb0 + n_sb) * (32 * S) > a.n || (int64_t)(group0 + n_groups) * (DENSE_TILES_PER_GROUP * 32) > a.m) {
+        dense_workgroup<CT, 24>(a, lds_row_keys, lds_col_keys, lds_tops);
+        return;
+    }
+
+    const char* d1 = a.d1 + (int64_t)b * a.d1_bstride;
+    const char* d2 = a.d2 + (int64_t)b * a.d2_bstride;
+    u64* row_keys = a.row_keys + (int64_t)b * a.n;
+    u64* col_keys = a.col_keys + (int64_t)b * a.m;
+
+    DenseStream stream;
+    stream.d1 = d1 + (int64_t)sb0 * S * (32 * 48);
+    stream.n_sb = n_sb;
+    stream.total = n_groups * n_sb * DENSE_TURNS;
+
+    dense_stage_turn(slot0, stream.turn(0), wave, lane);
+    for (int i = threadIdx.x; i < S * 32; i += blockDim.x) lds_row_keys[i] = 0;
+    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
+    __syncthreads();
+    dense_stage_turn(slot1, stream.turn(1), wave, lane);
+
+    int k = 0;  // stream turn the next sweep starts with
+    for (int g = 0; g < n_groups; ++g) {
+        const int tbase = ((group0 + g) * DENSE_WAVES + wave) * J;  // this wave's first candidate tile (all inside the map)
+        Frag cand[J];
+#pragma unroll
+        for (int jt = 0; jt < J; ++jt) {
+            cand[jt] = O::load(d2 + ((int64_t)(tbase + jt) * 32 + c) * O::ROW_BYTES, h);
+            lds_col_keys[jt * 32 + c] = 0;
+        }
+
+        for (int sb = 0; sb < n_sb; ++sb, k += DENSE_TURNS) {
+            const int sbg = sb0 + sb;
+            float cmax[J][16];
+#pragma unroll
+            for (int jt = 0; jt < J; ++jt)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) cmax[jt][v] = ninf;
+
+            dense_sweep_staged<CT>(a, cand, cmax, slot0, slot1, stream, k, lds_row_keys + sb * S * 32, tbase / J, wave, lane);
+
+            dense_flush_columns(cmax, lds_tops, lds_col_keys, sbg, lane, h, held);
+        }
+
 #pragma unroll
         for (int jt = 0; jt < J; ++jt) {
             const int j = (tbase + jt) * 32 + c;
@@ -589,7 +856,13 @@ static hipError_t launch_dense_t(const DenseArgs& a, int batch, int32_t* nn12, f
     dim3 grid((groups + a.groups_per_wg - 1) / a.groups_per_wg, (a.n_sb + a.sb_per_wg - 1) / a.sb_per_wg, batch);
     const size_t lds_bytes = ((size_t)a.sb_per_wg * DENSE_S * 32 + DENSE_WAVES * DENSE_J * 32) * sizeof(u64) +
                              DENSE_WAVES * 32 * sizeof(float);  // row keys, column keys, 32 maxima per wave
-    hipError_t e = launch(TK_DENSE, dense_kernel<CT, DP>, grid, dim3(DENSE_WAVES * 64), lds_bytes, s, a);
+    hipError_t e;
+    if constexpr (DENSE_STAGED && CT != CT_F32 && DP == 24) {
+        if (a.sb_per_wg != 1) return hipErrorInvalidValue;  // the staged kernel's key table holds one super-block
+        e = launch_detail(TK_DENSE, 1, dense_staged_kernel<CT>, grid, dim3(DENSE_WAVES * 64), 0, s, a);
+    } else {
+        e = launch(TK_DENSE, dense_kernel<CT, DP>, grid, dim3(DENSE_WAVES * 64), lds_bytes, s, a);
+    }
     if (e != hipSuccess) return e;
     const int most = a.n > a.m ? a.n : a.m;
     const size_t hist_bytes = ((size_t)a.row_units + a.col_units) * sizeof(int);

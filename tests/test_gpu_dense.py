@@ -106,3 +106,17 @@ def test_strided_half_storage_and_nearest_agreement():
     check_exact({k: host(v) for k, v in out.items()}, 0, ref)
     assert np.array_equal(host(gi)[0], ref["nn12"]) and np.array_equal(host(gs)[0], ref["s12"])
     assert np.array_equal(host(gj)[0], ref["nn21"])
+
+
+@pytest.mark.parametrize("compute,d,staged", [("f16", 24, True), ("bf16", 24, True), ("f32", 24, False), ("f16", 16, False), ("f16", 32, False)])
+def test_which_pass1_kernel_ran(compute, d, staged):
+    """16-bit rows of 24 channels take the kernel that stages the query blocks through LDS (trace detail
+    1), everything else the one with per-wave loads; a shape with interior workgroups (staged sweep) and
+    edge workgroups (padding: unstaged sweep inside the same kernel) is bit-exact either way."""
+    a, b = exact_maps(77, 9000, 5000, d)
+    fnn.fnn_trace_begin(64)
+    got = run_dense([a], [b], compute)
+    trace = fnn.fnn_trace_end(64, details=True)
+    details = [detail for name, _, detail in trace if name == "dense_kernel"]
+    assert details == [1 if staged else 0]
+    check_exact(got, 0, oracle.mutual_dense(a, b))
