@@ -406,6 +406,11 @@ def main() -> int:
         ta, tb = torch.from_numpy(a).to(dev), torch.from_numpy(b).to(dev)
         ts = seeds[:1].contiguous()
         o1 = fnn.fnn_reciprocal(ta, tb, ts, MAX_ITER, compute, workspace=ws)
+        # untimed calls first: the host thread has just slept through the long ceiling kernels, and on
+        # some boxes its core takes tens of milliseconds to clock up again -- until then the 52 launches
+        # of a call take the host longer to enqueue than the device needs to run them
+        for _ in range(200):
+            fnn.fnn_reciprocal(ta, tb, ts, MAX_ITER, compute, out=o1, workspace=ws)
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         for _ in range(50):

@@ -33,6 +33,11 @@ COMMANDS = {line.split()[0]: line.split(None, 1)[1] for line in __doc__.splitlin
             if line.startswith("    ") and " rocprofv3 " in line}
 
 
+def is_dense_pass1(name):
+    """The pass-1 kernel of the dense mode, whichever variant ran."""
+    return "dense_staged_kernel<" in name or "dense_kernel<" in name
+
+
 def short(name: str) -> str:
     name = name.replace("(anonymous namespace)::", "").replace("void fnn::", "").replace("fnn::", "")
     return name.split("(")[0]
@@ -81,7 +86,7 @@ def kernel_stats() -> None:
         d = [(int(r["End_Timestamp"]) - int(r["Start_Timestamp"])) / 1e3 for r in trace if pred(r)]
         return (sum(d) / len(d), len(d)) if d else (float("nan"), 0)
     sk_us, sk_n = avg_us(lambda r: "search_kernel" in r["Kernel_Name"] and int(r.get("Grid_Size_Y") or 0) == 16)
-    dk = [r for r in stats if "dense_kernel<" in r["Name"] or short(r["Name"]).startswith("dense_kernel")]
+    dk = [r for r in stats if is_dense_pass1(r["Name"])]
     lines += ["", "## Agreement with bench.py (same run, its own HIP-event timing)", ""]
     if sk_n:
         lines.append(f"* search_kernel, launches of the 16-pair batch: kernel-trace average {sk_us:.2f} us over {sk_n} launches; bench.py "
@@ -138,7 +143,9 @@ def hbm_traffic() -> None:
         wr = sum(w[0]) / len(w[0]) * cal["write"] * 1024
         return rd, wr, f[0]
     s_rd, s_wr, s_list = kernel_bytes("search_kernel")
-    d_rd, d_wr, _ = kernel_bytes("dense_kernel")
+    d_rd, d_wr, _ = kernel_bytes("dense_staged_kernel")
+    if d_rd is None:
+        d_rd, d_wr, _ = kernel_bytes("dense_kernel")
     result = {"source": f"profiles/hbm_traffic_{SUFFIX}.md (rocprofv3 FETCH_SIZE + WRITE_SIZE, scaled by a 256 MiB copy)"}
     if s_rd is not None and bench:
         # bench.py runs its batched reciprocal steps first: one call that builds the outputs, the
@@ -170,7 +177,8 @@ def hbm_traffic() -> None:
                   f"search_kernel read {sum(live)/max(len(live),1):.1f} MiB on average (the last-level cache keeps part of a map between the searches "
                   "of a step), the launches after the last seed has converged read nothing.", ""]
     if d_rd is not None:
-        d_us = times.get([k for k in times if k.startswith("dense_kernel")][0]) if any(k.startswith("dense_kernel") for k in times) else None
+        d_names = [k for k in times if k.startswith("dense_staged_kernel")] or [k for k in times if k.startswith("dense_kernel")]
+        d_us = times.get(d_names[0]) if d_names else None
         rate = ""
         if d_us:
             t = sum(d_us) / len(d_us)
@@ -203,7 +211,7 @@ def mfma_utilisation() -> None:
     if not searches:
         searches = sorted([(k, v) for k, v in disp.items() if "search_kernel" in k[1]], key=lambda kv: -kv[1].get("SQ_INSTS_MFMA", 0))
         first_name = "search_kernel"
-    denses = [(k, v) for k, v in disp.items() if "dense_kernel<" in k[1]]
+    denses = [(k, v) for k, v in disp.items() if is_dense_pass1(k[1])]
     if not searches or not denses:
         return
     sk, dk = searches[min(2, len(searches) - 1)], denses[-1]
@@ -255,7 +263,7 @@ def lds_l2() -> None:
     kernels = [("search_first_kernel", "max", "search_first_kernel, first search of a step (fp32 maps in, LDS-staged)"),
                ("search_kernel", "max", "search_kernel, largest launch (third search of a step: 16 x ~1450 queries)"),
                ("resolve_kernel", "max", "resolve_kernel, first resolve of a step"),
-               ("dense_kernel<", "mean", "dense_kernel (cfg 3)"), ("prep_f32_kernel", "max", "prepare pass, largest launch (the dense legs: both maps of a pair)")]
+               ("dense_staged_kernel<", "mean", "dense_staged_kernel (cfg 3; query blocks staged through LDS)"), ("prep_f32_kernel", "max", "prepare pass, largest launch (the dense legs: both maps of a pair)")]
     lines = ["# LDS and cache counters (rocprofv3 SQ / TCP / TCC counters): bench.py workloads", "", "Commands (two counter runs):", "",
              "    " + COMMANDS["lds"], "    " + COMMANDS["l2"], "",
              "Per dispatch; SQ_BUSY_CYCLES is summed over the shader engines, the cache counters over all channels.", "",
