@@ -323,8 +323,13 @@ void search_first_kernel(FirstSearchArgs fa) {
 #pragma unroll
         for (int p = 0; p < FIRST_AHEAD; ++p) raw[p] = Tile::fetch(fa, tgt, b, t0 + p * FIRST_TURN + wave, t1, c, h);
 
+        // The running best of a query block lives in two registers that trade places from tile to
+        // tile (the tiles of a turn are unrolled, so which one is current is known at compile time):
+        // the fold writes the new best beside the old one, which the "did it rise" test still needs,
+        // instead of into a scratch register that then has to be copied.
+        static_assert(FIRST_TURN % 2 == 0, "after a turn the current best is in best[0] again");
         Frag q[G][R];
-        float best[G][R];
+        float best[2][G][R];
         int best_tile[G][R];
         bool live[G];
 #pragma unroll
@@ -336,7 +341,8 @@ void search_first_kernel(FirstSearchArgs fa) {
                 const int64_t row = slot < n_act ? query_row(a, qbase, slot) : 0;
                 if (fa.raw_queries) q[g][r] = O::round_raw(O::load_raw(fa.raw_src.map[b] + row * fa.raw_src.row_stride, h));
                 else q[g][r] = O::load(src + row * O::ROW_BYTES, h);
-                best[g][r] = ninf;
+                best[0][g][r] = ninf;
+                best[1][g][r] = ninf;
                 best_tile[g][r] = 0x7FFFFFFF;
             }
         }
@@ -354,6 +360,7 @@ void search_first_kernel(FirstSearchArgs fa) {
 #pragma unroll
             for (int j = 0; j < FIRST_TURN; ++j) {
                 const int t = t0 + k * FIRST_TURN + j;
+                const int now = j & 1, then = now ^ 1;
                 if (t < t1) {  // uniform
                     Frag cur;
                     cur.lo = stage_lo[SLOT][j][lane];
@@ -374,12 +381,17 @@ void search_first_kernel(FirstSearchArgs fa) {
                             }
 #pragma unroll
                             for (int r = 0; r < R; ++r) {
-                                const float top = fold16(best[g][r], acc[r]);
-                                if (top > best[g][r]) best_tile[g][r] = t;
-                                best[g][r] = top;
+                                const float top = fold16(best[now][g][r], acc[r]);
+                                if (top > best[now][g][r]) best_tile[g][r] = t;
+                                best[then][g][r] = top;
                             }
                         }
                     }
+                } else {  // past the chunk's last tile: the best just moves on
+#pragma unroll
+                    for (int g = 0; g < G; ++g)
+#pragma unroll
+                        for (int r = 0; r < R; ++r) best[then][g][r] = best[now][g][r];
                 }
             }
         };
@@ -392,14 +404,15 @@ void search_first_kernel(FirstSearchArgs fa) {
         for (int g = 0; g < G; ++g)
 #pragma unroll
             for (int r = 0; r < R; ++r) {
-                const float ob = __shfl_xor(best[g][r], 32);
+                float mine = best[0][g][r];
+                const float ob = __shfl_xor(mine, 32);
                 const int ot = __shfl_xor(best_tile[g][r], 32);
-                if (ob > best[g][r] || (ob == best[g][r] && ot < best_tile[g][r])) {
-                    best[g][r] = ob;
+                if (ob > mine || (ob == mine && ot < best_tile[g][r])) {
+                    mine = ob;
                     best_tile[g][r] = ot;
                 }
                 const int slot = slot0 + (g * R + r) * 32 + c;
-                if (h == 0 && slot < n_act) atomicMax(&a.out_keys[qbase + slot], pack_key(best[g][r], best_tile[g][r]));
+                if (h == 0 && slot < n_act) atomicMax(&a.out_keys[qbase + slot], pack_key(mine, best_tile[g][r]));
             }
         __syncthreads();  // the next unit's first turn reuses ring slot 0
     }
