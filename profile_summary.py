@@ -5,11 +5,11 @@ The raw output comes from these commands, run on the MI355X machine from the reposit
 (`python profile_summary.py --commands` prints them; each counter set is a run of its own):
 
     stats  rocprofv3 --kernel-trace --stats --output-format csv -d gpurun_out/prof_stats -o bench -- python3 bench.py --no-cfg5
-    fetch  rocprofv3 --pmc FETCH_SIZE --kernel-trace --output-format csv -d gpurun_out/prof_fetch -o bench -- python3 bench.py --no-cpu --no-cfg5 --no-ceiling --steps 5 --warmup 1 --copy-calibration
-    write  rocprofv3 --pmc WRITE_SIZE --kernel-trace --output-format csv -d gpurun_out/prof_write -o bench -- python3 bench.py --no-cpu --no-cfg5 --no-ceiling --steps 5 --warmup 1 --copy-calibration
-    mfma   rocprofv3 --pmc SQ_VALU_MFMA_BUSY_CYCLES SQ_VALU_MFMA_COEXEC_CYCLES SQ_INSTS_VALU SQ_INSTS_MFMA SQ_ACTIVE_INST_VALU SQ_BUSY_CYCLES SQ_WAVE_CYCLES SQ_WAIT_INST_ANY GRBM_GUI_ACTIVE --kernel-trace --output-format csv -d gpurun_out/prof_mfma -o bench -- python3 bench.py --no-cpu --no-cfg5 --no-ceiling --steps 5 --warmup 1
-    lds    rocprofv3 --pmc SQ_INSTS_LDS SQ_LDS_BANK_CONFLICT SQ_LDS_ADDR_CONFLICT SQ_ACTIVE_INST_LDS SQ_WAVES SQ_BUSY_CYCLES SQ_INSTS_VMEM_RD --kernel-trace --output-format csv -d gpurun_out/prof_lds -o bench -- python3 bench.py --no-cpu --no-cfg5 --no-ceiling --steps 5 --warmup 1
-    l2     rocprofv3 --pmc TCC_HIT_sum TCC_MISS_sum TCP_TCC_READ_REQ_sum TCP_TOTAL_CACHE_ACCESSES_sum --kernel-trace --output-format csv -d gpurun_out/prof_l2 -o bench -- python3 bench.py --no-cpu --no-cfg5 --no-ceiling --steps 5 --warmup 1
+    fetch  rocprofv3 --pmc FETCH_SIZE --kernel-trace --output-format csv -d gpurun_out/prof_fetch -o bench -- python3 bench.py --no-cpu --no-cfg5 --no-ceiling --no-latency --steps 5 --warmup 1 --copy-calibration
+    write  rocprofv3 --pmc WRITE_SIZE --kernel-trace --output-format csv -d gpurun_out/prof_write -o bench -- python3 bench.py --no-cpu --no-cfg5 --no-ceiling --no-latency --steps 5 --warmup 1 --copy-calibration
+    mfma   rocprofv3 --pmc SQ_VALU_MFMA_BUSY_CYCLES SQ_VALU_MFMA_COEXEC_CYCLES SQ_INSTS_VALU SQ_INSTS_MFMA SQ_ACTIVE_INST_VALU SQ_BUSY_CYCLES SQ_WAVE_CYCLES SQ_WAIT_INST_ANY GRBM_GUI_ACTIVE --kernel-trace --output-format csv -d gpurun_out/prof_mfma -o bench -- python3 bench.py --no-cpu --no-cfg5 --no-ceiling --no-latency --steps 5 --warmup 1
+    lds    rocprofv3 --pmc SQ_INSTS_LDS SQ_LDS_BANK_CONFLICT SQ_LDS_ADDR_CONFLICT SQ_ACTIVE_INST_LDS SQ_WAVES SQ_BUSY_CYCLES SQ_INSTS_VMEM_RD --kernel-trace --output-format csv -d gpurun_out/prof_lds -o bench -- python3 bench.py --no-cpu --no-cfg5 --no-ceiling --no-latency --steps 5 --warmup 1
+    l2     rocprofv3 --pmc TCC_HIT_sum TCC_MISS_sum TCP_TCC_READ_REQ_sum TCP_TOTAL_CACHE_ACCESSES_sum --kernel-trace --output-format csv -d gpurun_out/prof_l2 -o bench -- python3 bench.py --no-cpu --no-cfg5 --no-ceiling --no-latency --steps 5 --warmup 1
 
 Every run's bench.py line is expected next to its CSV files as gpurun_out/prof_<name>/bench.json
 (stdout of the command).  A summary is written for every run whose output is present.  The
