@@ -120,3 +120,15 @@ def test_which_pass1_kernel_ran(compute, d, staged):
     details = [detail for name, _, detail in trace if name == "dense_kernel"]
     assert details == [1 if staged else 0]
     check_exact(got, 0, oracle.mutual_dense(a, b))
+
+
+def test_staged_kernel_batch_and_several_groups_per_workgroup():
+    """The staged pass-1 kernel beyond the small shapes: a batch of two pairs with interior and edge
+    workgroups, and one pair large enough that a workgroup sweeps several candidate groups (the query
+    stream repeats per group) while its last super-block and last group still meet padding."""
+    pairs = [exact_maps(300 + b, 9000, 5000, 24) for b in range(2)]
+    got = run_dense([p[0] for p in pairs], [p[1] for p in pairs], "f16")
+    for b in range(2):
+        check_exact(got, b, oracle.mutual_dense(*pairs[b]))
+    a, b = exact_maps(41, 150000, 30000, 24)
+    check_exact(run_dense([a], [b], "bf16"), 0, oracle.mutual_dense(a, b))
