@@ -273,15 +273,14 @@ struct DenseSlot {
 
 #define FNN_LDS_PTR(p) ((void __attribute__((address_space(3)))*)(p))
 
-// This wave's two blocks of the turn that starts at `turn` (uniform; 48-byte rows) into `slot`.
+// This wave's two blocks of the turn that starts at `turn` (uniform; 48-byte rows) into slot `st`.
 // A direct load writes lane l's bytes at the LDS base + l * size: 16 bytes per lane give the
 // `lo` words in lane order; the `hi` words (8 bytes per reading lane) take two 4-byte loads in
 // which lane l fetches word l & 1 of reading lane l >> 1 (first half) or 32 + (l >> 1).
-__device__ __forceinline__ void dense_stage_turn(DenseSlot& st, const char* turn, int wave, int lane) {
+__device__ __forceinline__ void dense_stage_turn(DenseSlot& st, const char* turn, int wave) {
     // The lane number is read afresh and the byte offsets are recomputed from it (a few
     // operations per turn): held across the sweep they were spilled, and a reload behind the
     // loads issued here would wait for all of them.
-    (void)lane;
     uint32_t l;
     asm volatile("v_mbcnt_lo_u32_b32 %0, -1, 0\n\tv_mbcnt_hi_u32_b32 %0, -1, %0" : "=v"(l));
     const uint32_t c = l & 31, h = l >> 5, pair = l >> 1, word = l & 1;
@@ -375,7 +374,7 @@ __device__ __forceinline__ void dense_sweep_staged(const DenseArgs& a, const typ
                 for (int done = 0; done + 1 < DENSE_TURN_STEPS; ++done) file_row_best(done, tt * DENSE_TURN_BLOCKS + 2 * done);
                 __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0): this wave's share of the next turn is in LDS
                 __syncthreads();
-                dense_stage_turn(mine, stream.turn(k0 + tt + 2), wave, lane);
+                dense_stage_turn(mine, stream.turn(k0 + tt + 2), wave);
                 q[other][0] = staged(next, 0, o16);
                 q[other][1] = staged(next, 1, o16);
             }
@@ -451,11 +450,11 @@ void dense_staged_kernel(DenseArgs a) {
     stream.n_sb = n_sb;
     stream.total = n_groups * n_sb * DENSE_TURNS;
 
-    dense_stage_turn(slot0, stream.turn(0), wave, lane);
+    dense_stage_turn(slot0, stream.turn(0), wave);
     for (int i = threadIdx.x; i < S * 32; i += blockDim.x) lds_row_keys[i] = 0;
     __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
     __syncthreads();
-    dense_stage_turn(slot1, stream.turn(1), wave, lane);
+    dense_stage_turn(slot1, stream.turn(1), wave);
 
     int k = 0;  // stream turn the next sweep starts with
     for (int g = 0; g < n_groups; ++g) {
