@@ -85,15 +85,19 @@ def kernel_stats() -> None:
     def avg_us(pred):
         d = [(int(r["End_Timestamp"]) - int(r["Start_Timestamp"])) / 1e3 for r in trace if pred(r)]
         return (sum(d) / len(d), len(d)) if d else (float("nan"), 0)
-    sk_us, sk_n = avg_us(lambda r: "search_kernel" in r["Kernel_Name"] and int(r.get("Grid_Size_Y") or 0) == 16)
+    sk_us, sk_n = avg_us(lambda r: ("search_kernel" in r["Kernel_Name"] or "search_first_kernel" in r["Kernel_Name"])
+                         and int(r.get("Grid_Size_Y") or 0) == 16)
     dk = [r for r in stats if is_dense_pass1(r["Name"])]
     lines += ["", "## Agreement with bench.py (same run, its own HIP-event timing)", ""]
     if sk_n:
-        lines.append(f"* search_kernel, launches of the 16-pair batch: kernel-trace average {sk_us:.2f} us over {sk_n} launches; bench.py "
+        lines.append(f"* search launches of the 16-pair batch (search_kernel and search_first_kernel together, as in bench.py's `roofline`): "
+                     f"kernel-trace average {sk_us:.2f} us over {sk_n} launches; bench.py "
                      f"`roofline.avg_launch_ms` = {bench['roofline']['avg_launch_ms']*1e3:.2f} us over its traced launches (the profiler's "
-                     "average also covers the warm-up and untraced timed steps, whose launches are the same mix).")
+                     "average also covers the warm-up and untraced timed steps, whose launches are the same mix; the HIP events of bench.py bracket "
+                     "each dispatch, so they add a few microseconds per launch, which shows in the 12 launches of a step that find nothing to do: "
+                     "the bench line's fraction is the conservative one).")
     if dk and "dense_mutual" in bench:
-        lines.append(f"* dense_kernel: rocprofv3 average {float(dk[0]['AverageNs'])/1e3:.1f} us; bench.py "
+        lines.append(f"* dense pass-1 kernel: rocprofv3 average {float(dk[0]['AverageNs'])/1e3:.1f} us (minimum {float(dk[0]['MinNs'])/1e3:.1f}; the first calls run on cold clocks); bench.py "
                      f"`dense_mutual.roofline.avg_launch_ms` = {bench['dense_mutual']['roofline']['avg_launch_ms']*1e3:.1f} us.")
     lines += ["", "## bench.py line of this run", "",
               f"Under the profiler every launch takes longer to dispatch, so this line's {bench['ms_per_step']:.2f} ms per step is above an "
