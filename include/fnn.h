@@ -48,10 +48,11 @@
  *    d in {16, 24, 32} (16-bit formats) or a multiple of 8 (FNN_F32), row_stride == d, n a
  *    multiple of 32, 16-byte aligned, the batch's maps equally spaced in memory, no flags --
  *    then fnn_nearest and fnn_reciprocal search it where it is;
- *    (b) fnn_reciprocal on fp32 maps with d == 24, a 16-bit compute format, no flags, rows
- *    that start on 16-byte boundaries (row_stride a multiple of 4), at least 1536 seeds and
- *    enough work per pair: the first forward and the first backward search read the caller's
- *    rows, round them on the way and leave the prepared copy behind for the later searches.
+ *    (b) fnn_reciprocal and (without nq_active) fnn_nearest on fp32 maps with d == 24, a
+ *    16-bit compute format, no flags, rows that start on 16-byte boundaries (row_stride a
+ *    multiple of 4), at least 1536 seeds or queries and enough work per pair: the first forward
+ *    and the first backward search (the one search of fnn_nearest) read the caller's rows, round
+ *    them on the way and leave the prepared copy behind for the passes that follow.
  *  - Errors are return codes only.  Argument errors are detected on the host before
  *    anything is enqueued (outputs untouched).  Index arrays live in device memory and are
  *    NOT range-checked: a seed or query index outside [0, n) is undefined behaviour.

@@ -205,15 +205,19 @@ bool direct_layout(int32_t batch, const fnn_map* maps, const fnn_opts* opts, int
 // Caller maps that the fused first searches can read where they are (they round the fp32 rows
 // themselves and write the prepared copy as a by-product): plain fp32 rows of 24 channels that
 // start on 16-byte boundaries, a 16-bit compute format, no options, enough queries.
-bool raw_first_search(int32_t batch, const fnn_map* a, const fnn_map* b, const fnn_opts* opts, int64_t n_queries) {
-    if (opts->flags != 0 || (opts->compute != FNN_F16 && opts->compute != FNN_BF16)) return false;
-    if (!first_search_applies(n_queries, a[0].n, batch) || !first_search_applies(n_queries, b[0].n, batch)) return false;
-    for (const fnn_map* maps : {a, b})
-        for (int i = 0; i < batch; ++i)
-            if (maps[i].dtype != FNN_F32 || maps[i].d != 24 || maps[i].row_stride % 4 != 0 || maps[i].n <= 0 ||
-                ((uintptr_t)maps[i].data % 16) != 0)
-                return false;
+bool raw_rows(int32_t batch, const fnn_map* maps) {
+    for (int i = 0; i < batch; ++i)
+        if (maps[i].dtype != FNN_F32 || maps[i].d != 24 || maps[i].row_stride % 4 != 0 || maps[i].n <= 0 ||
+            ((uintptr_t)maps[i].data % 16) != 0)
+            return false;
     return true;
+}
+bool raw_options(const fnn_opts* opts) {
+    return opts->flags == 0 && (opts->compute == FNN_F16 || opts->compute == FNN_BF16);
+}
+bool raw_first_search(int32_t batch, const fnn_map* a, const fnn_map* b, const fnn_opts* opts, int64_t n_queries) {
+    return raw_options(opts) && first_search_applies(n_queries, a[0].n, batch) && first_search_applies(n_queries, b[0].n, batch) &&
+           raw_rows(batch, a) && raw_rows(batch, b);
 }
 void fill_raw(RawMaps& r, int32_t batch, const fnn_map* maps) {
     memset(&r, 0, sizeof(r));
@@ -369,7 +373,13 @@ int32_t fnn_nearest(int32_t batch, const fnn_map* src, const int32_t* q_idx, int
     int64_t bs1 = L.maps.bstride1, bs2 = L.maps.bstride2;
     const bool direct1 = direct_layout(batch, src, opts, L.maps.dp, &p1, &bs1);
     const bool direct2 = direct_layout(batch, tgt, opts, L.maps.dp, &p2, &bs2);
-    FNN_TRY(prep_both(batch, src, tgt, L.maps, d, opts, s, extra, false, direct1, direct2));
+    // With every query live and enough of them, the search runs in the kernel that stages the
+    // candidate tiles through LDS; fp32 maps of the paper's shape are then read where they are (no
+    // prepare pass: the search leaves the prepared candidates behind for the resolve pass).
+    const bool staged_shape = !nq_active && first_search_applies(nq, m, batch);
+    const bool fused = staged_shape && raw_options(opts) && raw_rows(batch, src) && raw_rows(batch, tgt);
+    const bool staged = fused || (staged_shape && L.maps.dp == 24 && opts->compute != FNN_F32);
+    FNN_TRY(prep_both(batch, src, tgt, L.maps, d, opts, s, extra, false, direct1 || fused, direct2 || fused));
     SearchArgs sa;
     memset(&sa, 0, sizeof(sa));
     sa.src = p1;
@@ -383,7 +393,24 @@ int32_t fnn_nearest(int32_t batch, const fnn_map* src, const int32_t* q_idx, int
     sa.m = (int32_t)m;
     sa.m_tiles = (int32_t)(L.maps.m_pad / 32);
     sa.out_keys = L.keys;
-    FNN_TRY(launch_search(sa, batch, opts->compute, L.maps.dp, s));
+    if (staged) {
+        FirstSearchArgs first;
+        memset(&first, 0, sizeof(first));
+        first.s = sa;
+        if (fused) {
+            first.s.src_rows = (int32_t)n;  // query rows are clamped to the caller's map, which has no padding rows
+            fill_raw(first.raw_tgt, batch, tgt);
+            fill_raw(first.raw_src, batch, src);
+            first.raw_queries = 1;
+        }
+        FNN_TRY(launch_search_first(first, batch, opts->compute, s));
+        if (fused) {
+            FNN_TRY(launch_resolve_raw(first, batch, opts->compute, out_idx, out_score, s));
+            return FNN_OK;
+        }
+    } else {
+        FNN_TRY(launch_search(sa, batch, opts->compute, L.maps.dp, s));
+    }
     FNN_TRY(launch_resolve(sa, batch, opts->compute, L.maps.dp, out_idx, out_score, s));
     return FNN_OK;
 }
@@ -553,7 +580,7 @@ static int32_t reciprocal_impl(int32_t batch, const fnn_map* d1, const fnn_map* 
         fill_raw(first.raw_src, batch, d1);
         first.raw_queries = 1;
         FNN_TRY(launch_search_first(first, batch, compute, s));
-        FNN_TRY(launch_resolve_raw(first, batch, compute, s));
+        FNN_TRY(launch_resolve_raw(first, batch, compute, nullptr, nullptr, s));
     } else if (staged) {
         FirstSearchArgs first;
         memset(&first, 0, sizeof(first));

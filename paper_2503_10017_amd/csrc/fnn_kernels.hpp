@@ -131,7 +131,7 @@ struct FirstSearchArgs {
 bool first_search_applies(int64_t nq, int64_t m, int batch);
 hipError_t launch_search_first(const FirstSearchArgs& a, int batch, int compute, hipStream_t s);
 // launch_resolve with the queries still in the caller's fp32 map
-hipError_t launch_resolve_raw(const FirstSearchArgs& a, int batch, int compute, hipStream_t s);
+hipError_t launch_resolve_raw(const FirstSearchArgs& a, int batch, int compute, int32_t* out_idx, float* out_score, hipStream_t s);
 // Pass 2: out_keys become (best score, lowest candidate index); optionally also stored to
 // out_idx / out_score (either may be NULL).  Queries without any candidate get -1 / -inf.
 hipError_t launch_resolve(const SearchArgs& a, int batch, int compute, int dp, int32_t* out_idx, float* out_score,

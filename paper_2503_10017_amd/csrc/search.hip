@@ -482,9 +482,9 @@ void resolve_kernel(SearchArgs a, int32_t* out_idx, float* out_score) {
 // fused first search rounds them).
 template <int CT>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2)))
-void resolve_raw_kernel(FirstSearchArgs fa) {
+void resolve_raw_kernel(FirstSearchArgs fa, int32_t* out_idx, float* out_score) {
     using O = Ops<CT, 24>;
-    resolve_body<CT, 24>(fa.s, nullptr, nullptr, [&](int b, int64_t row, int h) {
+    resolve_body<CT, 24>(fa.s, out_idx, out_score, [&](int b, int64_t row, int h) {
         return O::round_raw(O::load_raw(fa.raw_src.map[b] + row * fa.raw_src.row_stride, h));
     });
 }
@@ -633,13 +633,13 @@ hipError_t launch_search_first(const FirstSearchArgs& a, int batch, int compute,
     return hipErrorInvalidValue;
 }
 
-hipError_t launch_resolve_raw(const FirstSearchArgs& a, int batch, int compute, hipStream_t s) {
+hipError_t launch_resolve_raw(const FirstSearchArgs& a, int batch, int compute, int32_t* out_idx, float* out_score, hipStream_t s) {
     if (a.s.nq <= 0 || batch <= 0) return hipSuccess;
     int wgs = (a.s.nq + 3) / 4;
     const int cap = 2048 / batch > 64 ? 2048 / batch : 64;
     if (wgs > cap) wgs = cap;
-    if (compute == FNN_F16) return launch(TK_RESOLVE, resolve_raw_kernel<CT_F16>, dim3(wgs, batch), dim3(256), 0, s, a);
-    if (compute == FNN_BF16) return launch(TK_RESOLVE, resolve_raw_kernel<CT_BF16>, dim3(wgs, batch), dim3(256), 0, s, a);
+    if (compute == FNN_F16) return launch(TK_RESOLVE, resolve_raw_kernel<CT_F16>, dim3(wgs, batch), dim3(256), 0, s, a, out_idx, out_score);
+    if (compute == FNN_BF16) return launch(TK_RESOLVE, resolve_raw_kernel<CT_BF16>, dim3(wgs, batch), dim3(256), 0, s, a, out_idx, out_score);
     return hipErrorInvalidValue;
 }
 

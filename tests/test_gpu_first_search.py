@@ -114,3 +114,50 @@ def test_single_large_pair_is_staged():
     got, searches, _ = traced_reciprocal(dev(a), dev(b), dev(seeds), "bf16")
     assert searches[:2] == [STAGED, STAGED]
     check_reciprocal_exact(got, 0, oracle.reciprocal(a, b, seeds[0], 10))
+
+
+def traced_nearest(t1, t2, compute, q_idx=None):
+    fnn.fnn_trace_begin(16)
+    try:
+        idx, score = fnn.fnn_nearest(t1, t2, q_idx=q_idx, compute=compute)
+        torch.cuda.synchronize()
+    finally:
+        trace = fnn.fnn_trace_end(16, details=True)
+    return host(idx), host(score), [d for name, _, d in trace if name == "search_kernel"], [ms for name, ms, _ in trace if name == "prep_kernel"]
+
+
+@pytest.mark.parametrize("compute", ["f16", "bf16"])
+def test_nearest_takes_the_staged_kernel_when_every_query_is_live(compute):
+    """fnn_nearest with enough queries: fp32 maps are searched where they are (staged kernel, no prepare
+    pass over the maps), with and without a query list; maps in another storage format are prepared
+    first and then take the same kernel; few queries, or a live count on the device, keep the
+    ordinary one.  Exact inputs: indices and scores equal the oracle's bit for bit every time."""
+    rng = np.random.default_rng(5)
+    n, m, batch = 4100, 6401, 64
+    a = [exact(rng, n, 28) for _ in range(batch)]
+    b = [exact(rng, m, 28) for _ in range(batch)]
+    t1 = [dev(x)[:, :24] for x in a]
+    t2 = [dev(x)[:, :24] for x in b]
+    ref_all = [oracle.nearest(a[p][:, :24], b[p][:, :24]) for p in (0, 40, 63)]
+
+    idx, score, searches, prep_ms = traced_nearest(t1, t2, compute)            # every pixel of image 1 is a query
+    assert searches == [STAGED]
+    for k, p in enumerate((0, 40, 63)):
+        assert np.array_equal(idx[p], ref_all[k][0]) and np.array_equal(score[p], ref_all[k][1])
+
+    q = rng.integers(0, n, size=(batch, 1700)).astype(np.int32)
+    idx, score, searches, _ = traced_nearest(t1, t2, compute, dev(q))
+    assert searches == [STAGED]
+    for k, p in enumerate((0, 40, 63)):
+        assert np.array_equal(idx[p], ref_all[k][0][q[p]]) and np.array_equal(score[p], ref_all[k][1][q[p]])
+
+    tdt = torch.float16 if compute == "f16" else torch.bfloat16
+    idx, score, searches, _ = traced_nearest([x.to(tdt) for x in t1], [x.to(tdt) for x in t2], compute, dev(q))   # strided 16-bit rows: prepared first
+    assert searches == [STAGED]
+    for k, p in enumerate((0, 40, 63)):
+        assert np.array_equal(idx[p], ref_all[k][0][q[p]]) and np.array_equal(score[p], ref_all[k][1][q[p]])
+
+    idx, score, searches, _ = traced_nearest(t1, t2, compute, dev(q[:, :1000]))    # too few queries for a quad of row groups
+    assert STAGED not in searches
+    for k, p in enumerate((0, 40, 63)):
+        assert np.array_equal(idx[p], ref_all[k][0][q[p, :1000]])
