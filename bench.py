@@ -80,6 +80,8 @@ def main() -> int:
                     help="also time the same batch with the squared-distance dist_func (FNN_FLAG_L2)")
     ap.add_argument("--split", action="store_true",
                     help="also time the batch with FNN_FLAG_SPLIT (fp32-grade scores from three fp16 products) and with fp32 products")
+    ap.add_argument("--nearest", action="store_true",
+                    help="also time fnn_nearest on the same batch: the 3072 seeds of every pair as queries, and every pixel as a query")
     ap.add_argument("--batch-sweep", action="store_true",
                     help="also time the same workload at 1, 2, 4, 8, 32 and 64 pairs per call")
     ap.add_argument("--no-ceiling", action="store_true",
@@ -327,6 +329,26 @@ def main() -> int:
             "note": "same 16 pairs, score = -|a-b|^2/2 through 4 extra channels (rows of 32 instead of 24 channels)",
         }
         del lws
+
+    # ---- optional: one-directional search (fnn_nearest) on the same batch ------------------------------
+    if args.nearest:
+        nws = torch.empty(fnn.fnn_workspace_bytes(BATCH, N_PIX, N_PIX, D, N_PIX, compute), dtype=torch.uint8, device=dev)
+        legs = {}
+        for name, kw, reps in (("seeds_as_queries", {"q_idx": seeds}, args.steps), ("every_pixel_a_query", {}, max(args.steps // 10, 2))):
+            for _ in range(2):
+                fnn.fnn_nearest(d1, d2, compute=compute, workspace=nws, **kw)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(reps):
+                fnn.fnn_nearest(d1, d2, compute=compute, workspace=nws, **kw)
+            torch.cuda.synchronize()
+            n_s = (time.perf_counter() - t0) / reps
+            nq = n_seeds if kw else N_PIX
+            legs[name] = {"ms_per_call": round(n_s * 1e3, 4), "queries_per_pair": nq,
+                          "tflops": round(2.0 * D * N_PIX * nq * BATCH / n_s / 1e12, 1)}
+        legs["note"] = "fnn_nearest on the 16 pairs, fp32 maps in: image-1 queries against every pixel of image 2"
+        result["nearest_batch"] = legs
+        del nws
 
     # ---- optional: the same workload at other batch sizes ---------------------------------------------
     if args.batch_sweep:
